@@ -1,0 +1,274 @@
+/*
+ * psx.h -- C ABI of the chunked mixed-precision Adam path for MI355X (gfx950).
+ *
+ * The operations are those of PatrickStar (arXiv 2108.05818): model data is
+ * packed, in model-initialisation order, into chunks of one fixed element
+ * count; four chunk lists (param fp16, param fp32, momentum, variance) share
+ * one tensor->(chunk, offset) map; gradients in fp16 sit in the param fp16
+ * slots (or in a chunk list of their own); the ADAM stage converts the fp16
+ * gradient chunk to fp32 on the fly, updates the fp32 states and writes the
+ * fp16 parameter chunk back.  Optimizer-state chunks may live in GPU memory
+ * or in pinned host memory, chunk by chunk.
+ *
+ * Conventions
+ *   - Every call returns a psx status (0 = PSX_OK, negative = error).  No
+ *     exception or abort crosses the boundary.  psx_last_error() gives the
+ *     calling thread's last message.  Argument errors are detected before any
+ *     payload byte is touched.
+ *   - "host" pointers are ordinary process memory.  "device" pointers are HIP
+ *     device allocations on the current device.  "pinned" pointers are
+ *     page-locked host allocations (hipHostMalloc or equivalent).
+ *   - The caller owns every payload buffer (tensors, chunks).  The library
+ *     owns only what psx_ctx_create() allocates: descriptor tables, flags,
+ *     staging tiles, side streams and events.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *     Calls enqueue work on it and return; they are asynchronous unless the
+ *     description says the call synchronises.  A context must not be used
+ *     from two threads at once.
+ *   - Chunk base addresses must be 16-byte aligned.  Tensor addresses need
+ *     only their element alignment.
+ *   - Element counts are in elements, never bytes.
+ */
+#ifndef PSX_H
+#define PSX_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* ------------------------------------------------------------------ status */
+#define PSX_OK          0
+#define PSX_EINVAL     (-1)  /* null pointer, zero chunk size, bad enum, ...          */
+#define PSX_ETOOLARGE  (-2)  /* tensor larger than a chunk under PSX_LAYOUT_STRICT    */
+#define PSX_ECAP       (-3)  /* an output array or a context table is too small       */
+#define PSX_EALIGN     (-4)  /* a chunk base is not 16-byte aligned                   */
+#define PSX_EHIP       (-5)  /* the HIP runtime reported an error (see last error)    */
+#define PSX_ENOSTAGING (-6)  /* host-resident chunk given to a context without staging */
+
+/* Message of the last failing call on this thread ("" if none). Host pointer, owned by the library. */
+const char *psx_last_error(void);
+
+/* ------------------------------------------------------------------ layout
+ * Tensor-Chunk-Mapper (Sec. "Preprocessing Stage"): tensors are appended in
+ * the given order into chunks of chunk_elems elements; the same map serves
+ * the param fp16, param fp32, momentum and variance lists.  A tensor that
+ * does not fit the rest of the current chunk opens the next chunk; the rest
+ * stays an unused fragment at the chunk's tail.  A tensor is never split to
+ * fill a fragment.  A tensor larger than a whole chunk (the paper avoids it
+ * by choosing the chunk size) starts on a fresh chunk and runs over as many
+ * consecutive chunks as it needs, unless PSX_LAYOUT_STRICT asks for the
+ * paper's behaviour, in which case it is PSX_ETOOLARGE.  A zero-element
+ * tensor gets the current position and takes no space.
+ */
+typedef struct psx_slot {
+    uint32_t chunk;     /* index of the chunk holding the tensor's first element */
+    uint32_t reserved;  /* 0 */
+    uint64_t offset;    /* element offset inside that chunk */
+    uint64_t numel;     /* elements; may run past the chunk end for an oversized tensor */
+} psx_slot;
+
+#define PSX_LAYOUT_STRICT 1u
+
+/*
+ * numel[n]   host, in : element count of each tensor, in model-initialisation order
+ * slots[n]   host, out: may be NULL (sizing call)
+ * used[cap]  host, out: filled prefix of each chunk, elements; may be NULL
+ * n_chunks   host, out: number of chunks (>= 1)
+ * Pure host code, deterministic, touches no GPU.  If used != NULL and cap is
+ * smaller than the chunk count the call fails with PSX_ECAP (outputs unspecified).
+ */
+int32_t psx_chunk_layout(const uint64_t *numel, size_t n, uint64_t chunk_elems, uint32_t flags,
+                         psx_slot *slots, uint64_t *used, size_t cap, size_t *n_chunks);
+
+/* ------------------------------------------------------------------ context */
+typedef struct psx_ctx psx_ctx;
+
+typedef struct psx_ctx_config {
+    uint64_t max_chunks;          /* most chunks any call will pass                          */
+    uint64_t max_tensors;         /* most tensors any pack/unpack call will pass             */
+    uint64_t staging_tile_elems;  /* elements per staging tile for host-resident chunks;     */
+                                  /* 0 = no staging (host-resident chunks are refused)       */
+    uint32_t staging_slots;       /* tiles in flight, 2..8 (ignored when tile_elems == 0)    */
+    uint32_t reserved;            /* 0 */
+} psx_ctx_config;
+
+/* Allocates the context on the current HIP device: descriptor tables, the
+ * overflow flags, 3 * staging_slots * staging_tile_elems floats of device
+ * staging, two side streams (default priority) and events.  Synchronous. */
+int32_t psx_ctx_create(const psx_ctx_config *cfg, psx_ctx **out);
+/* Waits for the context's outstanding work, then frees what create allocated. */
+int32_t psx_ctx_destroy(psx_ctx *ctx);
+
+/* ------------------------------------------------------------------ pack / unpack
+ * Tensor <-> chunk copies (Sec. "Training Stage": a tensor's data is the piece
+ * of chunk payload its slot names; after BWD the fp16 gradient is copied from
+ * temporary memory into the slot of its param fp16 tensor).  Bit-exact copies;
+ * fragments are neither read nor written.  The chunk list is one virtual
+ * array of n_chunks*chunk_elems elements, so an oversized tensor runs on into
+ * the following chunk(s).
+ *
+ * dtype         PSX_F16 (2-byte elements) or PSX_F32 (4-byte elements)
+ * tensors[n]    host array of device pointers, tensor i has slots[i].numel elements
+ * slots[n]      host, from psx_chunk_layout
+ * chunks[]      host array of n_chunks device pointers, each chunk_elems elements
+ * flags         PSX_PACK_CHECK_OVERFLOW (psx_pack, PSX_F16 only): while copying,
+ *               OR the inf/nan test of every copied element into the context's
+ *               overflow flags (see psx_overflow_check; clear them first with
+ *               psx_overflow_reset)
+ * One multi-tensor launch on `stream`; asynchronous.  The descriptor upload
+ * may wait for the context's previous upload to finish.
+ */
+#define PSX_F16 1u
+#define PSX_F32 2u
+#define PSX_PACK_CHECK_OVERFLOW 1u
+
+int32_t psx_pack(psx_ctx *ctx, uint32_t dtype, const void *const *tensors, const psx_slot *slots,
+                 size_t n, void *const *chunks, size_t n_chunks, uint64_t chunk_elems,
+                 uint32_t flags, void *stream);
+int32_t psx_unpack(psx_ctx *ctx, uint32_t dtype, void *const *tensors, const psx_slot *slots,
+                   size_t n, const void *const *chunks, size_t n_chunks, uint64_t chunk_elems,
+                   uint32_t flags, void *stream);
+
+/* ------------------------------------------------------------------ overflow flag
+ * Mixed-precision training with loss scaling (the paper's mixed-precision
+ * citation) skips the update when any gradient is inf or nan.  The test is
+ * taken on the fp16 bit pattern: all five exponent bits set.  Only the first
+ * used[c] elements of chunk c are looked at.
+ *
+ * g16_chunks[]  host array of n_chunks device pointers (fp16 gradient chunks)
+ * used[]        host array, elements in use per chunk
+ * per_chunk     host, out, n_chunks entries of 0/1; may be NULL
+ * flag_out      host, out, OR over all chunks; may be NULL
+ * The flags are first cleared, then computed on `stream` and left in the
+ * context on the device, where psx_chunk_adam_step(PSX_STEP_USE_FLAG) reads
+ * them.  If per_chunk or flag_out is non-NULL the call synchronises `stream`
+ * to read them back; otherwise it is asynchronous.
+ */
+int32_t psx_overflow_check(psx_ctx *ctx, const void *const *g16_chunks, const uint64_t *used,
+                           size_t n_chunks, uint32_t *per_chunk, uint32_t *flag_out, void *stream);
+/* Clear the context's flags on `stream` (asynchronous). */
+int32_t psx_overflow_reset(psx_ctx *ctx, void *stream);
+/* Read the context's flags back (synchronises `stream`).  per_chunk may be NULL. */
+int32_t psx_overflow_read(psx_ctx *ctx, uint32_t *per_chunk, size_t n_chunks, uint32_t *flag_out,
+                          void *stream);
+
+/* ------------------------------------------------------------------ Adam step
+ * ADAM stage over a chunk list (Sec. "Training Stage", last paragraph; Adam is
+ * Kingma & Ba's Algorithm 1 with bias correction, epsilon added outside the
+ * root; fp32 arithmetic, every operation rounded on its own, no fused
+ * multiply-add).  Step-wide scalars are derived in double from the doubles
+ * below and rounded to fp32 once:
+ *   step_size = lr/(1-beta1^t), c2 = 1/sqrt(1-beta2^t), inv_scale = 1/loss_scale,
+ *   beta1, beta2, 1-beta1, 1-beta2, eps, weight_decay, decay = 1-lr*weight_decay.
+ * Per element k < used:
+ *   g = f32(g16[k]) * inv_scale
+ *   weight_decay != 0, adamw_mode == 0:  g = g + weight_decay*p      (L2)
+ *   weight_decay != 0, adamw_mode != 0:  p = p * decay               (decoupled)
+ *   m = beta1*m + (1-beta1)*g ;  v = beta2*v + ((1-beta2)*g)*g
+ *   p = p - step_size * (m / (sqrt(v)*c2 + eps))
+ *   p16[k] = fp16 round-to-nearest-even of p
+ */
+typedef struct psx_adam_hyper {
+    double lr, beta1, beta2, eps, weight_decay, loss_scale;
+    uint64_t step;        /* 1-based index t of this update */
+    uint32_t adamw_mode;  /* 0 = L2 decay added to the gradient, 1 = decoupled decay */
+    uint32_t reserved;    /* 0 */
+} psx_adam_hyper;
+
+#define PSX_LOC_HBM  0u   /* fp32 states in device memory  */
+#define PSX_LOC_HOST 1u   /* fp32 states in pinned host memory */
+
+/*
+ * One chunk of the four lists.  g16 and p16 are always device memory; p16 may
+ * equal g16 (the paper's chunk reuse: the gradient sits in the param fp16
+ * chunk and is overwritten by the new fp16 parameters).  The fp32 states are
+ * found at entry in the loc_in buffers and left, updated, in the loc_out
+ * buffers (Sec. "Device-aware Operator Placement": as many optimizer-state
+ * chunks as fit stay in GPU memory, the rest in host memory):
+ *   HBM  -> HBM  : updated in place in p32/m/v.
+ *   HOST -> HOST : streamed tile by tile through the context's staging
+ *                  (H2D, update, D2H); p32/m/v may be NULL.
+ *   HOST -> HBM  : copied into p32/m/v, updated there (chunk admitted).
+ *   HBM  -> HOST : updated in p32/m/v, then copied to the host buffers (chunk
+ *                  evicted; the device buffers keep a copy the caller may drop).
+ */
+typedef struct psx_chunk {
+    void *g16;        /* device, fp16 gradients, chunk_elems capacity, first `used` read */
+    void *p16;        /* device, fp16 parameters out; may alias g16 */
+    void *p32, *m, *v;                  /* device fp32 states, or NULL if never in HBM  */
+    void *p32_host, *m_host, *v_host;   /* pinned fp32 states, or NULL if never on host */
+    uint64_t used;    /* elements in use (a prefix); the tail fragment is never touched */
+    uint8_t loc_in;   /* PSX_LOC_* where the states are at entry */
+    uint8_t loc_out;  /* PSX_LOC_* where they must be at exit    */
+    uint8_t reserved[6];
+} psx_chunk;
+
+#define PSX_STEP_USE_FLAG    1u  /* skip the update if the context's overflow flag is set      */
+#define PSX_STEP_CHECK_FIRST 2u  /* run the overflow check over all g16 chunks first (implies  */
+                                 /* PSX_STEP_USE_FLAG)                                         */
+/*
+ * chunks[n_chunks]  host array.  All work is enqueued on `stream` and on the
+ * context's two copy streams; on return `stream` has been made to wait for
+ * them, so work enqueued on `stream` afterwards sees the finished step.
+ * Asynchronous with respect to the host.
+ * Skipped step (flag set): p32/m/v keep their bits (states that change
+ * residence are still moved); p16 is left alone unless it aliases g16, in which
+ * case it is rewritten with fp16(p32) so that the chunk holds parameters again.
+ */
+int32_t psx_chunk_adam_step(psx_ctx *ctx, const psx_chunk *chunks, size_t n_chunks,
+                            const psx_adam_hyper *hyper, uint32_t flags, void *stream);
+
+/* ------------------------------------------------------------------ loss scale
+ * Dynamic loss scale bookkeeping on the host (a convention of mixed-precision
+ * training; not specified by the paper): an overflow halves the scale (floor 1),
+ * clears good_steps and leaves step unchanged; otherwise step and good_steps
+ * advance and growth_interval good steps in a row double the scale.
+ */
+typedef struct psx_scaler {
+    float scale;
+    uint32_t growth_interval;
+    uint32_t good_steps;
+    uint32_t reserved;
+    uint64_t step;        /* t of the next update to apply; starts at 1 */
+} psx_scaler;
+
+int32_t psx_loss_scale_update(psx_scaler *s, uint32_t overflow);
+
+/* ------------------------------------------------------------------ tuning and timing
+ * Launch shape knobs (for sweeps; defaults are tuned for MI355X):
+ *   PSX_TUNE_ADAM_BLOCKS_PER_CU  resident workgroups per CU of the Adam kernel (0 = one tile per workgroup)
+ *   PSX_TUNE_ADAM_UNROLL         rows of 4 elements per thread per tile: 1, 2 or 4
+ *   PSX_TUNE_NONTEMPORAL         0/1: non-temporal hints on the streaming loads and stores
+ *   PSX_TUNE_COPY_BLOCKS_PER_CU  same as the first, for pack/unpack/check
+ */
+#define PSX_TUNE_ADAM_BLOCKS_PER_CU 1u
+#define PSX_TUNE_ADAM_UNROLL        2u
+#define PSX_TUNE_NONTEMPORAL        3u
+#define PSX_TUNE_COPY_BLOCKS_PER_CU 4u
+int32_t psx_ctx_set_tuning(psx_ctx *ctx, uint32_t key, int64_t value);
+
+/* Kernel timing with HIP events on the caller's stream (off by default). */
+typedef struct psx_timing {
+    float pack_ms;     /* last psx_pack / psx_unpack copy kernel                           */
+    float check_ms;    /* last overflow check kernel                                       */
+    float adam_ms;     /* last resident (HBM->HBM) Adam kernel launch                      */
+    float spill_ms;    /* last streamed part: first H2D issued to last D2H done            */
+    uint64_t adam_elems;   /* elements the resident launch covered                         */
+    uint64_t spill_elems;  /* elements of chunks with a host side                          */
+    uint64_t h2d_bytes, d2h_bytes;  /* link bytes of the streamed part                     */
+} psx_timing;
+int32_t psx_ctx_set_profiling(psx_ctx *ctx, int32_t on);
+/* Synchronises the recorded events, then fills *out (fields of phases not run are 0). */
+int32_t psx_ctx_get_timing(psx_ctx *ctx, psx_timing *out);
+
+/* Plain device copy of n_bytes (a multiple of 16, 16-byte aligned pointers), the
+ * reference kernel the bandwidth counters and the Adam kernel are scaled against. */
+int32_t psx_copy_bytes(psx_ctx *ctx, void *dst, const void *src, uint64_t n_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PSX_H */

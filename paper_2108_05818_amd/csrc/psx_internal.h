@@ -1,0 +1,79 @@
+// Internal declarations shared by the host runtime and the kernel launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "psx.h"
+
+namespace psx {
+
+// ---- error reporting (thread-local message behind psx_last_error) ----
+int32_t fail(int32_t code, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
+#define PSX_HIP(call)                                                                     \
+    do {                                                                                  \
+        hipError_t e_ = (call);                                                           \
+        if (e_ != hipSuccess)                                                             \
+            return ::psx::fail(PSX_EHIP, "%s -> %s (%s:%d)", #call, hipGetErrorString(e_), \
+                               __FILE__, __LINE__);                                       \
+    } while (0)
+
+// ---- device-side descriptors ----
+
+// One contiguous run of elements handled by the element-wise kernels.  Runs are
+// cut into tiles; tile_begin is the index of the run's first tile in the launch.
+struct AdamRun {
+    const uint16_t *g16;
+    uint16_t *p16;
+    float *p, *m, *v;
+    uint64_t n;
+    uint64_t tile_begin;
+    uint32_t chunk;      // index into the per-chunk overflow flags
+    uint32_t pad;
+};
+
+struct CopySeg {
+    const void *src;
+    void *dst;
+    uint64_t n;          // elements
+    uint64_t tile_begin;
+    uint32_t chunk;      // destination (pack) chunk index, for the fused overflow test
+    uint32_t pad;
+};
+
+// Step-wide fp32 scalars of the Adam update, prepared on the host in double.
+struct AdamScalars {
+    float step_size, c2, inv_scale, beta1, beta2, omb1, omb2, eps, wd, decay;
+    uint32_t decay_mode;   // 0 none, 1 L2 into the gradient, 2 decoupled
+};
+
+struct Tuning {
+    int adam_blocks_per_cu = 8;
+    int adam_unroll = 2;
+    int nontemporal = 1;
+    int copy_blocks_per_cu = 8;
+};
+
+// Elements per tile of the Adam kernel for a given unroll (256 threads x 4 elements x unroll).
+constexpr uint32_t kThreads = 256;
+inline uint64_t adam_tile_elems(int unroll) { return (uint64_t)kThreads * 4u * (uint64_t)unroll; }
+constexpr uint64_t kCheckTileElems = (uint64_t)kThreads * 8u * 4u;   // 8192 fp16 per tile
+constexpr uint64_t kCopyTileBytes = (uint64_t)kThreads * 16u * 4u;   // 16 KiB per tile
+
+// ---- launchers (psx_kernels.hip).  All enqueue on `s` and return the launch status. ----
+hipError_t launch_adam(const AdamRun *runs_dev, uint32_t n_runs, uint64_t n_tiles,
+                       const AdamScalars &sc, const uint32_t *flag_dev, const Tuning &t,
+                       int n_cu, hipStream_t s);
+// skipped step with p16 aliasing g16: p16 = fp16(p32), only when *flag_dev != 0
+hipError_t launch_recast_if_flag(const AdamRun *runs_dev, uint32_t n_runs, uint64_t n_tiles,
+                                 const uint32_t *flag_dev, const Tuning &t, int n_cu, hipStream_t s);
+hipError_t launch_check(const AdamRun *runs_dev, uint32_t n_runs, uint64_t n_tiles,
+                        uint32_t *flag_dev, uint32_t *per_chunk_dev, const Tuning &t, int n_cu,
+                        hipStream_t s);
+hipError_t launch_copy(const CopySeg *segs_dev, uint32_t n_segs, uint64_t n_tiles,
+                       uint32_t elem_size, uint32_t *flag_dev, uint32_t *per_chunk_dev,
+                       const Tuning &t, int n_cu, hipStream_t s);
+hipError_t launch_fill_u32(uint32_t *dst, uint64_t n, uint32_t value, hipStream_t s);
+hipError_t launch_copy_bytes(void *dst, const void *src, uint64_t n_bytes, const Tuning &t,
+                             int n_cu, hipStream_t s);
+
+}  // namespace psx

@@ -1,0 +1,483 @@
+// HIP kernels for gfx950 (MI355X): fused chunk Adam, overflow check,
+// multi-tensor pack/unpack copy.  All of them are streaming, HBM-bound
+// element-wise passes: 64-wide wavefronts issue one 16-byte (fp32) or 8-byte
+// (fp16) access per lane and instruction, so every instruction of a wavefront
+// covers one contiguous 1 KiB / 512 B span; no LDS and no matrix cores are
+// involved because nothing is reused or contracted.
+//
+// Floating-point discipline (the results are compared bit for bit with a
+// scalar CPU statement of the same formulas): no contraction into fused
+// multiply-add, IEEE-correct division and square root (hipcc's default for
+// HIP), denormals kept, round-to-nearest-even conversions.
+#include "psx_internal.h"
+
+#pragma clang fp contract(off)
+
+namespace psx {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint16_t u16x4 __attribute__((ext_vector_type(4)));
+
+// Pointers read from a descriptor table are generic; every buffer of this
+// library is global memory, and saying so lets the compiler emit global_load /
+// global_store instead of flat accesses.
+#define PSX_GLOBAL __attribute__((address_space(1)))
+template <typename V, typename T>
+__device__ __forceinline__ const PSX_GLOBAL V *gptr(const T *p) {
+    return (const PSX_GLOBAL V *)(p);
+}
+template <typename V, typename T>
+__device__ __forceinline__ PSX_GLOBAL V *gptr(T *p) {
+    return (PSX_GLOBAL V *)(p);
+}
+
+template <bool NT, typename T>
+__device__ __forceinline__ T ld(const PSX_GLOBAL T *p) {
+    if constexpr (NT) return __builtin_nontemporal_load(p);
+    else return *p;
+}
+template <bool NT, typename T>
+__device__ __forceinline__ void st(PSX_GLOBAL T *p, T v) {
+    if constexpr (NT) __builtin_nontemporal_store(v, p);
+    else *p = v;
+}
+
+// Index of the run (or segment) that owns `tile`: the last one whose
+// tile_begin is <= tile.  Uniform across the workgroup, so the loads go
+// through the scalar unit.
+template <typename D>
+__device__ __forceinline__ uint32_t find_owner(const D *__restrict__ d, uint32_t n, uint64_t tile) {
+    uint32_t lo = 0, hi = n;
+    while (hi - lo > 1) {
+        uint32_t mid = (lo + hi) >> 1;
+        if (d[mid].tile_begin <= tile) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// ------------------------------------------------------------------ Adam
+
+// One element of the update, in the operation order of include/psx.h.
+template <int DM>
+__device__ __forceinline__ void adam_elem(float g, float &p, float &m, float &v,
+                                          const AdamScalars &s) {
+    g = g * s.inv_scale;
+    if constexpr (DM == 1) {
+        float t = s.wd * p;
+        g = g + t;
+    } else if constexpr (DM == 2) {
+        p = p * s.decay;
+    }
+    float a = s.beta1 * m;
+    float b = s.omb1 * g;
+    m = a + b;
+    float c = s.beta2 * v;
+    float d = s.omb2 * g;
+    float e = d * g;
+    v = c + e;
+    float r = __builtin_sqrtf(v);
+    float den = r * s.c2;
+    den = den + s.eps;
+    float q = m / den;
+    float u = s.step_size * q;
+    p = p - u;
+}
+
+template <int U, bool NT, int DM>
+__global__ __launch_bounds__(kThreads) void adam_kernel(const AdamRun *__restrict__ runs,
+                                                        uint32_t n_runs, uint64_t n_tiles,
+                                                        AdamScalars sc,
+                                                        const uint32_t *__restrict__ flag) {
+    if (flag != nullptr && *flag != 0) return;          // overflow: the whole step is skipped
+    constexpr uint32_t ROW = kThreads * 4;
+    constexpr uint32_t TILE = ROW * U;
+    const uint32_t tid = threadIdx.x;
+    for (uint64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const uint32_t r = find_owner(runs, n_runs, tile);
+        const uint16_t *g16 = runs[r].g16;
+        uint16_t *p16 = runs[r].p16;
+        float *pp = runs[r].p, *pm = runs[r].m, *pv = runs[r].v;
+        const uint64_t n = runs[r].n;
+        const uint64_t base = (tile - runs[r].tile_begin) * TILE;
+        if (n - base >= TILE) {
+            f16x4 g[U];
+            f32x4 p[U], m[U], v[U];
+#pragma unroll
+            for (int u = 0; u < U; u++) {
+                const uint64_t i = base + (uint64_t)u * ROW + tid * 4;
+                g[u] = ld<NT>(gptr<f16x4>(g16 + i));
+                p[u] = ld<NT>(gptr<f32x4>(pp + i));
+                m[u] = ld<NT>(gptr<f32x4>(pm + i));
+                v[u] = ld<NT>(gptr<f32x4>(pv + i));
+            }
+            f16x4 h[U];
+#pragma unroll
+            for (int u = 0; u < U; u++) {
+#pragma unroll
+                for (int k = 0; k < 4; k++) {
+                    float pk = p[u][k], mk = m[u][k], vk = v[u][k];
+                    adam_elem<DM>((float)g[u][k], pk, mk, vk, sc);
+                    p[u][k] = pk; m[u][k] = mk; v[u][k] = vk;
+                    h[u][k] = (_Float16)pk;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; u++) {
+                const uint64_t i = base + (uint64_t)u * ROW + tid * 4;
+                st<NT>(gptr<f32x4>(pp + i), p[u]);
+                st<NT>(gptr<f32x4>(pm + i), m[u]);
+                st<NT>(gptr<f32x4>(pv + i), v[u]);
+                st<NT>(gptr<f16x4>(p16 + i), h[u]);
+            }
+        } else {
+            // last, partial tile of a run: whole groups of 4 as above, then a scalar tail
+            for (int u = 0; u < U; u++) {
+                const uint64_t i = base + (uint64_t)u * ROW + tid * 4;
+                if (i + 4 <= n) {
+                    f16x4 g = *gptr<f16x4>(g16 + i);
+                    f32x4 p = *gptr<f32x4>(pp + i);
+                    f32x4 m = *gptr<f32x4>(pm + i);
+                    f32x4 v = *gptr<f32x4>(pv + i);
+                    f16x4 h;
+#pragma unroll
+                    for (int k = 0; k < 4; k++) {
+                        float pk = p[k], mk = m[k], vk = v[k];
+                        adam_elem<DM>((float)g[k], pk, mk, vk, sc);
+                        p[k] = pk; m[k] = mk; v[k] = vk;
+                        h[k] = (_Float16)pk;
+                    }
+                    *gptr<f32x4>(pp + i) = p;
+                    *gptr<f32x4>(pm + i) = m;
+                    *gptr<f32x4>(pv + i) = v;
+                    *gptr<f16x4>(p16 + i) = h;
+                } else {
+                    for (uint64_t k = i; k < n; k++) {
+                        float pk = *gptr<float>(pp + k), mk = *gptr<float>(pm + k), vk = *gptr<float>(pv + k);
+                        _Float16 gk = *gptr<_Float16>(g16 + k);
+                        adam_elem<DM>((float)gk, pk, mk, vk, sc);
+                        *gptr<float>(pp + k) = pk; *gptr<float>(pm + k) = mk; *gptr<float>(pv + k) = vk;
+                        *gptr<_Float16>(p16 + k) = (_Float16)pk;
+                    }
+                }
+            }
+        }
+    }
+}
+
+template <int U, bool NT>
+static hipError_t launch_adam_dm(const AdamRun *runs, uint32_t n_runs, uint64_t n_tiles,
+                                 const AdamScalars &sc, const uint32_t *flag, uint32_t grid,
+                                 hipStream_t s) {
+    switch (sc.decay_mode) {
+        case 0: hipLaunchKernelGGL((adam_kernel<U, NT, 0>), dim3(grid), dim3(kThreads), 0, s, runs, n_runs, n_tiles, sc, flag); break;
+        case 1: hipLaunchKernelGGL((adam_kernel<U, NT, 1>), dim3(grid), dim3(kThreads), 0, s, runs, n_runs, n_tiles, sc, flag); break;
+        default: hipLaunchKernelGGL((adam_kernel<U, NT, 2>), dim3(grid), dim3(kThreads), 0, s, runs, n_runs, n_tiles, sc, flag); break;
+    }
+    return hipGetLastError();
+}
+
+static uint32_t grid_for(uint64_t n_tiles, int blocks_per_cu, int n_cu) {
+    uint64_t cap = blocks_per_cu > 0 ? (uint64_t)blocks_per_cu * (uint64_t)n_cu : 0x7FFFFFFFull;
+    if (cap > 0x7FFFFFFFull) cap = 0x7FFFFFFFull;
+    uint64_t g = n_tiles < cap ? n_tiles : cap;
+    return (uint32_t)(g ? g : 1);
+}
+
+hipError_t launch_adam(const AdamRun *runs, uint32_t n_runs, uint64_t n_tiles, const AdamScalars &sc,
+                       const uint32_t *flag, const Tuning &t, int n_cu, hipStream_t s) {
+    if (n_tiles == 0) return hipSuccess;
+    const uint32_t grid = grid_for(n_tiles, t.adam_blocks_per_cu, n_cu);
+    const bool nt = t.nontemporal != 0;
+    switch (t.adam_unroll) {
+        case 1: return nt ? launch_adam_dm<1, true>(runs, n_runs, n_tiles, sc, flag, grid, s)
+                          : launch_adam_dm<1, false>(runs, n_runs, n_tiles, sc, flag, grid, s);
+        case 4: return nt ? launch_adam_dm<4, true>(runs, n_runs, n_tiles, sc, flag, grid, s)
+                          : launch_adam_dm<4, false>(runs, n_runs, n_tiles, sc, flag, grid, s);
+        default: return nt ? launch_adam_dm<2, true>(runs, n_runs, n_tiles, sc, flag, grid, s)
+                           : launch_adam_dm<2, false>(runs, n_runs, n_tiles, sc, flag, grid, s);
+    }
+}
+
+// ------------------------------------------------------------------ re-cast on a skipped step
+// Runs with the same tiling as the Adam kernel (unroll 2).  Does work only when the
+// overflow flag is set: the fp16 chunk, which held gradients, receives fp16(p32).
+__global__ __launch_bounds__(kThreads) void recast_kernel(const AdamRun *__restrict__ runs,
+                                                          uint32_t n_runs, uint64_t n_tiles,
+                                                          const uint32_t *__restrict__ flag) {
+    if (*flag == 0) return;
+    constexpr uint32_t ROW = kThreads * 4;
+    constexpr uint32_t TILE = ROW * 2;
+    const uint32_t tid = threadIdx.x;
+    for (uint64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const uint32_t r = find_owner(runs, n_runs, tile);
+        uint16_t *p16 = runs[r].p16;
+        const float *pp = runs[r].p;
+        const uint64_t n = runs[r].n;
+        const uint64_t base = (tile - runs[r].tile_begin) * TILE;
+        for (int u = 0; u < 2; u++) {
+            const uint64_t i = base + (uint64_t)u * ROW + tid * 4;
+            if (i + 4 <= n) {
+                f32x4 p = *gptr<f32x4>(pp + i);
+                f16x4 h;
+#pragma unroll
+                for (int k = 0; k < 4; k++) h[k] = (_Float16)p[k];
+                *gptr<f16x4>(p16 + i) = h;
+            } else {
+                for (uint64_t k = i; k < n; k++)
+                    *gptr<_Float16>(p16 + k) = (_Float16)*gptr<float>(pp + k);
+            }
+        }
+    }
+}
+
+hipError_t launch_recast_if_flag(const AdamRun *runs, uint32_t n_runs, uint64_t n_tiles,
+                                 const uint32_t *flag, const Tuning &t, int n_cu, hipStream_t s) {
+    if (n_tiles == 0) return hipSuccess;
+    const uint32_t grid = grid_for(n_tiles, t.adam_blocks_per_cu, n_cu);
+    hipLaunchKernelGGL(recast_kernel, dim3(grid), dim3(kThreads), 0, s, runs, n_runs, n_tiles, flag);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ overflow check
+// A 32-bit word holds two fp16 values; one of them is inf/nan iff its five exponent bits are all set.
+__device__ __forceinline__ uint32_t word_has_infnan(uint32_t w) {
+    const uint32_t t = w & 0x7C007C00u;
+    return (uint32_t)((t & 0xFFFFu) == 0x7C00u) | (uint32_t)((t >> 16) == 0x7C00u);
+}
+__device__ __forceinline__ uint32_t half_is_infnan(uint16_t h) { return (h & 0x7C00u) == 0x7C00u; }
+
+// A wavefront that saw an inf/nan raises the global and the per-chunk flag once
+// (ballot, then lane 0 writes); in the common all-finite case nothing is written.
+__device__ __forceinline__ void raise_flags(uint32_t bad, uint32_t *flag, uint32_t *per_chunk,
+                                            uint32_t chunk) {
+    const unsigned long long b = __ballot(bad != 0);
+    if (b != 0 && (threadIdx.x & 63u) == 0) {
+        atomicOr(flag, 1u);
+        if (per_chunk != nullptr) atomicOr(per_chunk + chunk, 1u);
+    }
+}
+
+template <bool NT>
+__global__ __launch_bounds__(kThreads) void check_kernel(const AdamRun *__restrict__ runs,
+                                                         uint32_t n_runs, uint64_t n_tiles,
+                                                         uint32_t *flag, uint32_t *per_chunk) {
+    constexpr uint32_t ROW = kThreads * 8;                // 8 fp16 = 16 bytes per lane
+    constexpr uint32_t TILE = ROW * 4;
+    static_assert(TILE == kCheckTileElems, "tile size");
+    const uint32_t tid = threadIdx.x;
+    for (uint64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const uint32_t r = find_owner(runs, n_runs, tile);
+        const uint16_t *g16 = runs[r].g16;
+        const uint64_t n = runs[r].n;
+        const uint64_t base = (tile - runs[r].tile_begin) * TILE;
+        uint32_t bad = 0;
+        if (n - base >= TILE) {
+            u32x4 w[4];
+#pragma unroll
+            for (int u = 0; u < 4; u++)
+                w[u] = ld<NT>(gptr<u32x4>(g16 + base + (uint64_t)u * ROW + tid * 8));
+#pragma unroll
+            for (int u = 0; u < 4; u++)
+#pragma unroll
+                for (int k = 0; k < 4; k++) bad |= word_has_infnan(w[u][k]);
+        } else {
+            for (int u = 0; u < 4; u++) {
+                const uint64_t i = base + (uint64_t)u * ROW + tid * 8;
+                if (i + 8 <= n) {
+                    u32x4 w = *gptr<u32x4>(g16 + i);
+#pragma unroll
+                    for (int k = 0; k < 4; k++) bad |= word_has_infnan(w[k]);
+                } else {
+                    for (uint64_t k = i; k < n; k++) bad |= half_is_infnan(*gptr<uint16_t>(g16 + k));
+                }
+            }
+        }
+        raise_flags(bad, flag, per_chunk, runs[r].chunk);
+    }
+}
+
+hipError_t launch_check(const AdamRun *runs, uint32_t n_runs, uint64_t n_tiles, uint32_t *flag,
+                        uint32_t *per_chunk, const Tuning &t, int n_cu, hipStream_t s) {
+    if (n_tiles == 0) return hipSuccess;
+    const uint32_t grid = grid_for(n_tiles, t.copy_blocks_per_cu, n_cu);
+    if (t.nontemporal)
+        hipLaunchKernelGGL(check_kernel<true>, dim3(grid), dim3(kThreads), 0, s, runs, n_runs, n_tiles, flag, per_chunk);
+    else
+        hipLaunchKernelGGL(check_kernel<false>, dim3(grid), dim3(kThreads), 0, s, runs, n_runs, n_tiles, flag, per_chunk);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ pack / unpack
+// One segment = one contiguous piece of a tensor inside one chunk.  A tile is
+// 16 KiB of it.  The destination is brought to 16-byte alignment with a few
+// single-element copies, then written with 16-byte stores; the source is read
+// with 16-byte loads when it happens to share that alignment, else with
+// 4-byte or 2-byte loads (every access is naturally aligned).
+template <int ES>
+struct ElemT;
+template <>
+struct ElemT<2> { typedef uint16_t type; };
+template <>
+struct ElemT<4> { typedef uint32_t type; };
+
+template <int ES, bool CHECK>
+__device__ __forceinline__ uint32_t test_vec(const u32x4 &w) {
+    if constexpr (CHECK && ES == 2)
+        return word_has_infnan(w[0]) | word_has_infnan(w[1]) | word_has_infnan(w[2]) | word_has_infnan(w[3]);
+    else
+        return 0;
+}
+
+template <int ES, bool CHECK, bool NT>
+__global__ __launch_bounds__(kThreads) void copy_kernel(const CopySeg *__restrict__ segs,
+                                                        uint32_t n_segs, uint64_t n_tiles,
+                                                        uint32_t *flag, uint32_t *per_chunk) {
+    typedef typename ElemT<ES>::type E;
+    constexpr uint32_t TILE_BYTES = (uint32_t)kCopyTileBytes;
+    constexpr uint32_t TILE_ELEMS = TILE_BYTES / ES;
+    const uint32_t tid = threadIdx.x;
+    for (uint64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const uint32_t r = find_owner(segs, n_segs, tile);
+        const uint64_t base = (tile - segs[r].tile_begin) * TILE_ELEMS;
+        const uint64_t left = segs[r].n - base;
+        const uint32_t cnt = left < TILE_ELEMS ? (uint32_t)left : TILE_ELEMS;
+        const unsigned char *s = static_cast<const unsigned char *>(segs[r].src) + base * ES;
+        unsigned char *d = static_cast<unsigned char *>(segs[r].dst) + base * ES;
+        const uint32_t nbytes = cnt * ES;
+        uint32_t bad = 0;
+        uint32_t head = (16u - (uint32_t)(reinterpret_cast<uintptr_t>(d) & 15u)) & 15u;
+        if (head > nbytes) head = nbytes;
+        const uint32_t mis = (uint32_t)(reinterpret_cast<uintptr_t>(s + head) & 15u);
+        if (head == 0 && mis == 0 && nbytes == TILE_BYTES) {
+            // whole aligned tile: four 16-byte loads in flight per lane, then four stores
+            u32x4 w[4];
+#pragma unroll
+            for (int u = 0; u < 4; u++)
+                w[u] = ld<NT>(gptr<u32x4>(s) + u * kThreads + tid);
+#pragma unroll
+            for (int u = 0; u < 4; u++) {
+                bad |= test_vec<ES, CHECK>(w[u]);
+                st<NT>(gptr<u32x4>(d) + u * kThreads + tid, w[u]);
+            }
+        } else {
+            const uint32_t head_e = head / ES;
+            if (tid < head_e) {
+                E x = gptr<E>(s)[tid];
+                if constexpr (CHECK && ES == 2) bad |= half_is_infnan(x);
+                gptr<E>(d)[tid] = x;
+            }
+            const unsigned char *sb = s + head;
+            unsigned char *db = d + head;
+            const uint32_t nvec = (nbytes - head) / 16u;
+            if (mis == 0) {
+                for (uint32_t i = tid; i < nvec; i += kThreads) {
+                    u32x4 w = gptr<u32x4>(sb)[i];
+                    bad |= test_vec<ES, CHECK>(w);
+                    gptr<u32x4>(db)[i] = w;
+                }
+            } else if ((mis & 3u) == 0) {
+                for (uint32_t i = tid; i < nvec; i += kThreads) {
+                    const PSX_GLOBAL uint32_t *q = gptr<uint32_t>(sb) + 4u * i;
+                    u32x4 w;
+                    w[0] = q[0]; w[1] = q[1]; w[2] = q[2]; w[3] = q[3];
+                    bad |= test_vec<ES, CHECK>(w);
+                    gptr<u32x4>(db)[i] = w;
+                }
+            } else {
+                // only 2-byte elements can be off by 2 modulo 4
+                for (uint32_t i = tid; i < nvec; i += kThreads) {
+                    const PSX_GLOBAL uint16_t *q = gptr<uint16_t>(sb) + 8u * i;
+                    u32x4 w;
+#pragma unroll
+                    for (int k = 0; k < 4; k++)
+                        w[k] = (uint32_t)q[2 * k] | ((uint32_t)q[2 * k + 1] << 16);
+                    bad |= test_vec<ES, CHECK>(w);
+                    gptr<u32x4>(db)[i] = w;
+                }
+            }
+            const uint32_t done = head + nvec * 16u;
+            const uint32_t tail_e = (nbytes - done) / ES;
+            if (tid < tail_e) {
+                E x = gptr<E>(s + done)[tid];
+                if constexpr (CHECK && ES == 2) bad |= half_is_infnan(x);
+                gptr<E>(d + done)[tid] = x;
+            }
+        }
+        if constexpr (CHECK) raise_flags(bad, flag, per_chunk, segs[r].chunk);
+    }
+}
+
+hipError_t launch_copy(const CopySeg *segs, uint32_t n_segs, uint64_t n_tiles, uint32_t elem_size,
+                       uint32_t *flag, uint32_t *per_chunk, const Tuning &t, int n_cu, hipStream_t s) {
+    if (n_tiles == 0) return hipSuccess;
+    const uint32_t grid = grid_for(n_tiles, t.copy_blocks_per_cu, n_cu);
+    const bool check = flag != nullptr;
+    const bool nt = t.nontemporal != 0;
+#define PSX_LAUNCH_COPY(ES, CH, NT_) \
+    hipLaunchKernelGGL((copy_kernel<ES, CH, NT_>), dim3(grid), dim3(kThreads), 0, s, segs, n_segs, n_tiles, flag, per_chunk)
+    if (elem_size == 2) {
+        if (check) { if (nt) PSX_LAUNCH_COPY(2, true, true); else PSX_LAUNCH_COPY(2, true, false); }
+        else       { if (nt) PSX_LAUNCH_COPY(2, false, true); else PSX_LAUNCH_COPY(2, false, false); }
+    } else {
+        if (nt) PSX_LAUNCH_COPY(4, false, true); else PSX_LAUNCH_COPY(4, false, false);
+    }
+#undef PSX_LAUNCH_COPY
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ small helpers
+__global__ void fill_u32_kernel(uint32_t *dst, uint64_t n, uint32_t value) {
+    for (uint64_t i = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x; i < n;
+         i += (uint64_t)gridDim.x * blockDim.x)
+        dst[i] = value;
+}
+
+hipError_t launch_fill_u32(uint32_t *dst, uint64_t n, uint32_t value, hipStream_t s) {
+    if (n == 0) return hipSuccess;
+    uint64_t blocks = (n + 255) / 256;
+    if (blocks > 1024) blocks = 1024;
+    hipLaunchKernelGGL(fill_u32_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, dst, n, value);
+    return hipGetLastError();
+}
+
+template <bool NT>
+__global__ __launch_bounds__(kThreads) void copy_bytes_kernel(u32x4 *__restrict__ dst,
+                                                              const u32x4 *__restrict__ src,
+                                                              uint64_t nvec) {
+    constexpr uint32_t TILE = kThreads * 4;
+    const uint64_t n_tiles = (nvec + TILE - 1) / TILE;
+    for (uint64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const uint64_t base = tile * TILE + threadIdx.x;
+        if (base - threadIdx.x + TILE <= nvec) {
+            u32x4 w[4];
+#pragma unroll
+            for (int u = 0; u < 4; u++) w[u] = ld<NT>(gptr<u32x4>(src + base + u * kThreads));
+#pragma unroll
+            for (int u = 0; u < 4; u++) st<NT>(gptr<u32x4>(dst + base + u * kThreads), w[u]);
+        } else {
+            for (int u = 0; u < 4; u++) {
+                const uint64_t i = base + u * kThreads;
+                if (i < nvec) dst[i] = src[i];
+            }
+        }
+    }
+}
+
+hipError_t launch_copy_bytes(void *dst, const void *src, uint64_t n_bytes, const Tuning &t, int n_cu,
+                             hipStream_t s) {
+    const uint64_t nvec = n_bytes / 16;
+    if (nvec == 0) return hipSuccess;
+    const uint64_t n_tiles = (nvec + kThreads * 4 - 1) / (kThreads * 4);
+    const uint32_t grid = grid_for(n_tiles, t.copy_blocks_per_cu, n_cu);
+    if (t.nontemporal)
+        hipLaunchKernelGGL(copy_bytes_kernel<true>, dim3(grid), dim3(kThreads), 0, s,
+                           static_cast<u32x4 *>(dst), static_cast<const u32x4 *>(src), nvec);
+    else
+        hipLaunchKernelGGL(copy_bytes_kernel<false>, dim3(grid), dim3(kThreads), 0, s,
+                           static_cast<u32x4 *>(dst), static_cast<const u32x4 *>(src), nvec);
+    return hipGetLastError();
+}
+
+}  // namespace psx

@@ -1,0 +1,646 @@
+// Host runtime behind the C ABI: context, descriptor tables, the multi-tensor
+// pack/unpack and overflow-check calls, and the Adam step with its
+// double-buffered H2D / update / D2H pipeline for host-resident chunks.
+#include <cmath>
+#include <cstring>
+#include <vector>
+
+#include "psx_internal.h"
+
+using namespace psx;
+
+namespace {
+
+constexpr int kRing = 4;        // pinned upload buffers per table
+
+// A descriptor table on the device, with the content last uploaded kept on the
+// host so that an unchanged table (the steady state of a training loop) is not
+// uploaded again.  Uploads are ordered on the caller's stream, after earlier
+// kernels that may still read the table.
+struct Table {
+    void *dev = nullptr;
+    size_t cap = 0;                       // bytes
+    std::vector<unsigned char> shadow;    // content on the device (as of the last enqueued upload)
+    void *pinned[kRing] = {nullptr, nullptr, nullptr, nullptr};
+    hipEvent_t done[kRing] = {nullptr, nullptr, nullptr, nullptr};
+    bool pending[kRing] = {false, false, false, false};
+    int next = 0;
+};
+
+int32_t table_free(Table &t) {
+    for (int i = 0; i < kRing; i++) {
+        if (t.pinned[i]) PSX_HIP(hipHostFree(t.pinned[i]));
+        if (t.done[i]) PSX_HIP(hipEventDestroy(t.done[i]));
+        t.pinned[i] = nullptr; t.done[i] = nullptr; t.pending[i] = false;
+    }
+    if (t.dev) PSX_HIP(hipFree(t.dev));
+    t.dev = nullptr; t.cap = 0; t.shadow.clear();
+    return PSX_OK;
+}
+
+int32_t table_reserve(Table &t, size_t bytes) {
+    if (bytes <= t.cap) return PSX_OK;
+    // growing is rare (first call with a larger list): drain the device, then reallocate
+    PSX_HIP(hipDeviceSynchronize());
+    int32_t rc = table_free(t);
+    if (rc != PSX_OK) return rc;
+    size_t cap = bytes + bytes / 2 + 4096;
+    PSX_HIP(hipMalloc(&t.dev, cap));
+    for (int i = 0; i < kRing; i++) {
+        PSX_HIP(hipHostMalloc(&t.pinned[i], cap, hipHostMallocDefault));
+        PSX_HIP(hipEventCreateWithFlags(&t.done[i], hipEventDisableTiming));
+    }
+    t.cap = cap;
+    return PSX_OK;
+}
+
+int32_t table_upload(Table &t, const void *data, size_t bytes, hipStream_t s) {
+    if (bytes == 0) return PSX_OK;
+    if (t.shadow.size() == bytes && memcmp(t.shadow.data(), data, bytes) == 0) return PSX_OK;
+    int32_t rc = table_reserve(t, bytes);
+    if (rc != PSX_OK) return rc;
+    const int k = t.next;
+    t.next = (t.next + 1) % kRing;
+    if (t.pending[k]) { PSX_HIP(hipEventSynchronize(t.done[k])); t.pending[k] = false; }
+    memcpy(t.pinned[k], data, bytes);
+    PSX_HIP(hipMemcpyAsync(t.dev, t.pinned[k], bytes, hipMemcpyHostToDevice, s));
+    PSX_HIP(hipEventRecord(t.done[k], s));
+    t.pending[k] = true;
+    t.shadow.assign(static_cast<const unsigned char *>(data), static_cast<const unsigned char *>(data) + bytes);
+    return PSX_OK;
+}
+
+struct TimedSpan {
+    hipEvent_t a = nullptr, b = nullptr;
+    bool valid = false;
+};
+
+}  // namespace
+
+struct psx_ctx {
+    int device = 0;
+    int n_cu = 0;
+    psx_ctx_config cfg{};
+    Tuning tune;
+    Table adam_tbl, check_tbl, pack_tbl, unpack_tbl;
+    uint32_t *flags_dev = nullptr;     // [0] global, [1 + c] chunk c
+    uint32_t *flags_host = nullptr;    // pinned read-back buffer
+    size_t flags_n = 0;
+    float *staging = nullptr;          // staging_slots x {p, m, v} x staging_tile_elems
+    hipStream_t h2d = nullptr, d2h = nullptr;
+    std::vector<hipEvent_t> ev_h2d, ev_k, ev_free;
+    hipEvent_t ev_entry = nullptr, ev_h2d_end = nullptr, ev_d2h_end = nullptr;
+    bool prof = false;
+    TimedSpan t_pack, t_check, t_adam, t_spill;
+    uint64_t adam_elems = 0, spill_elems = 0, h2d_bytes = 0, d2h_bytes = 0;
+    std::vector<AdamRun> runs;         // scratch for table building
+    std::vector<CopySeg> segs;
+};
+
+namespace {
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int32_t span_begin(psx_ctx *c, TimedSpan &t, hipStream_t s) {
+    t.valid = false;
+    if (!c->prof) return PSX_OK;
+    PSX_HIP(hipEventRecord(t.a, s));
+    return PSX_OK;
+}
+int32_t span_end(psx_ctx *c, TimedSpan &t, hipStream_t s) {
+    if (!c->prof) return PSX_OK;
+    PSX_HIP(hipEventRecord(t.b, s));
+    t.valid = true;
+    return PSX_OK;
+}
+
+int32_t set_device_guard(psx_ctx *c) {
+    int cur = -1;
+    PSX_HIP(hipGetDevice(&cur));
+    if (cur != c->device)
+        return fail(PSX_EINVAL, "context belongs to device %d but device %d is current", c->device, cur);
+    return PSX_OK;
+}
+
+// Append the runs of one chunk list section; returns the number of tiles.
+uint64_t push_run(std::vector<AdamRun> &v, const void *g16, void *p16, void *p, void *m, void *vv,
+                  uint64_t n, uint64_t tile_begin, uint64_t tile_elems, uint32_t chunk) {
+    AdamRun r;
+    r.g16 = static_cast<const uint16_t *>(g16);
+    r.p16 = static_cast<uint16_t *>(p16);
+    r.p = static_cast<float *>(p); r.m = static_cast<float *>(m); r.v = static_cast<float *>(vv);
+    r.n = n; r.tile_begin = tile_begin; r.chunk = chunk; r.pad = 0;
+    v.push_back(r);
+    return (n + tile_elems - 1) / tile_elems;
+}
+
+}  // namespace
+
+// ====================================================================== context
+
+extern "C" int32_t psx_ctx_create(const psx_ctx_config *cfg, psx_ctx **out) {
+    if (cfg == nullptr || out == nullptr) return fail(PSX_EINVAL, "psx_ctx_create: NULL argument");
+    *out = nullptr;
+    if (cfg->max_chunks == 0 || cfg->max_chunks > (1ull << 24))
+        return fail(PSX_EINVAL, "psx_ctx_create: max_chunks %llu out of range", (unsigned long long)cfg->max_chunks);
+    if (cfg->staging_tile_elems != 0) {
+        if (cfg->staging_slots < 2 || cfg->staging_slots > 8)
+            return fail(PSX_EINVAL, "psx_ctx_create: staging_slots must be 2..8");
+        if (cfg->staging_tile_elems % 8 != 0)
+            return fail(PSX_EINVAL, "psx_ctx_create: staging_tile_elems must be a multiple of 8");
+    }
+    psx_ctx *c = new psx_ctx();
+    c->cfg = *cfg;
+    auto bail = [&](int32_t rc) { psx_ctx_destroy(c); return rc; };
+#define PSX_TRY(call) do { hipError_t e_ = (call); if (e_ != hipSuccess) return bail(fail(PSX_EHIP, "%s -> %s", #call, hipGetErrorString(e_))); } while (0)
+    PSX_TRY(hipGetDevice(&c->device));
+    PSX_TRY(hipDeviceGetAttribute(&c->n_cu, hipDeviceAttributeMultiprocessorCount, c->device));
+    if (c->n_cu <= 0) c->n_cu = 256;
+    c->flags_n = 1 + (size_t)cfg->max_chunks;
+    PSX_TRY(hipMalloc(reinterpret_cast<void **>(&c->flags_dev), c->flags_n * sizeof(uint32_t)));
+    PSX_TRY(hipHostMalloc(reinterpret_cast<void **>(&c->flags_host), c->flags_n * sizeof(uint32_t), hipHostMallocDefault));
+    PSX_TRY(hipMemset(c->flags_dev, 0, c->flags_n * sizeof(uint32_t)));
+    PSX_TRY(hipStreamCreateWithFlags(&c->h2d, hipStreamNonBlocking));
+    PSX_TRY(hipStreamCreateWithFlags(&c->d2h, hipStreamNonBlocking));
+    PSX_TRY(hipEventCreateWithFlags(&c->ev_entry, hipEventDisableTiming));
+    PSX_TRY(hipEventCreateWithFlags(&c->ev_h2d_end, hipEventDisableTiming));
+    PSX_TRY(hipEventCreateWithFlags(&c->ev_d2h_end, hipEventDisableTiming));
+    const uint32_t ring = cfg->staging_tile_elems ? cfg->staging_slots : 2;
+    c->ev_h2d.resize(ring); c->ev_k.resize(ring); c->ev_free.resize(ring);
+    for (uint32_t i = 0; i < ring; i++) {
+        PSX_TRY(hipEventCreateWithFlags(&c->ev_h2d[i], hipEventDisableTiming));
+        PSX_TRY(hipEventCreateWithFlags(&c->ev_k[i], hipEventDisableTiming));
+        PSX_TRY(hipEventCreateWithFlags(&c->ev_free[i], hipEventDisableTiming));
+    }
+    for (TimedSpan *t : {&c->t_pack, &c->t_check, &c->t_adam, &c->t_spill}) {
+        PSX_TRY(hipEventCreate(&t->a));
+        PSX_TRY(hipEventCreate(&t->b));
+    }
+    if (cfg->staging_tile_elems) {
+        const size_t bytes = (size_t)3 * cfg->staging_slots * cfg->staging_tile_elems * sizeof(float);
+        PSX_TRY(hipMalloc(reinterpret_cast<void **>(&c->staging), bytes));
+    }
+#undef PSX_TRY
+    int32_t rc;
+    const size_t tiles_guess = cfg->staging_tile_elems ? 64 : 0;
+    if ((rc = table_reserve(c->adam_tbl, (3 * cfg->max_chunks + tiles_guess) * sizeof(AdamRun))) != PSX_OK) return bail(rc);
+    if ((rc = table_reserve(c->check_tbl, cfg->max_chunks * sizeof(AdamRun))) != PSX_OK) return bail(rc);
+    const size_t segs = (size_t)cfg->max_tensors + (size_t)cfg->max_chunks + 1;
+    if ((rc = table_reserve(c->pack_tbl, segs * sizeof(CopySeg))) != PSX_OK) return bail(rc);
+    if ((rc = table_reserve(c->unpack_tbl, segs * sizeof(CopySeg))) != PSX_OK) return bail(rc);
+    *out = c;
+    return PSX_OK;
+}
+
+extern "C" int32_t psx_ctx_destroy(psx_ctx *c) {
+    if (c == nullptr) return PSX_OK;
+    int32_t rc = PSX_OK;
+    auto note = [&](hipError_t e, const char *what) {
+        if (e != hipSuccess && rc == PSX_OK) rc = fail(PSX_EHIP, "psx_ctx_destroy: %s -> %s", what, hipGetErrorString(e));
+    };
+    note(hipDeviceSynchronize(), "hipDeviceSynchronize");
+    for (Table *t : {&c->adam_tbl, &c->check_tbl, &c->pack_tbl, &c->unpack_tbl}) {
+        int32_t r = table_free(*t);
+        if (r != PSX_OK && rc == PSX_OK) rc = r;
+    }
+    if (c->flags_dev) note(hipFree(c->flags_dev), "hipFree(flags)");
+    if (c->flags_host) note(hipHostFree(c->flags_host), "hipHostFree(flags)");
+    if (c->staging) note(hipFree(c->staging), "hipFree(staging)");
+    if (c->h2d) note(hipStreamDestroy(c->h2d), "hipStreamDestroy");
+    if (c->d2h) note(hipStreamDestroy(c->d2h), "hipStreamDestroy");
+    for (hipEvent_t e : {c->ev_entry, c->ev_h2d_end, c->ev_d2h_end})
+        if (e) note(hipEventDestroy(e), "hipEventDestroy");
+    for (auto *vec : {&c->ev_h2d, &c->ev_k, &c->ev_free})
+        for (hipEvent_t e : *vec)
+            if (e) note(hipEventDestroy(e), "hipEventDestroy");
+    for (TimedSpan *t : {&c->t_pack, &c->t_check, &c->t_adam, &c->t_spill}) {
+        if (t->a) note(hipEventDestroy(t->a), "hipEventDestroy");
+        if (t->b) note(hipEventDestroy(t->b), "hipEventDestroy");
+    }
+    delete c;
+    return rc;
+}
+
+extern "C" int32_t psx_ctx_set_tuning(psx_ctx *c, uint32_t key, int64_t value) {
+    if (c == nullptr) return fail(PSX_EINVAL, "psx_ctx_set_tuning: ctx is NULL");
+    switch (key) {
+        case PSX_TUNE_ADAM_BLOCKS_PER_CU:
+            if (value < 0 || value > 64) return fail(PSX_EINVAL, "adam blocks per CU must be 0..64");
+            c->tune.adam_blocks_per_cu = (int)value;
+            break;
+        case PSX_TUNE_ADAM_UNROLL:
+            if (value != 1 && value != 2 && value != 4) return fail(PSX_EINVAL, "adam unroll must be 1, 2 or 4");
+            c->tune.adam_unroll = (int)value;
+            break;
+        case PSX_TUNE_NONTEMPORAL:
+            c->tune.nontemporal = value != 0;
+            break;
+        case PSX_TUNE_COPY_BLOCKS_PER_CU:
+            if (value < 0 || value > 64) return fail(PSX_EINVAL, "copy blocks per CU must be 0..64");
+            c->tune.copy_blocks_per_cu = (int)value;
+            break;
+        default:
+            return fail(PSX_EINVAL, "psx_ctx_set_tuning: unknown key %u", key);
+    }
+    // tile sizes enter the cached tables: force a rebuild and upload
+    c->adam_tbl.shadow.clear();
+    return PSX_OK;
+}
+
+extern "C" int32_t psx_ctx_set_profiling(psx_ctx *c, int32_t on) {
+    if (c == nullptr) return fail(PSX_EINVAL, "psx_ctx_set_profiling: ctx is NULL");
+    c->prof = on != 0;
+    for (TimedSpan *t : {&c->t_pack, &c->t_check, &c->t_adam, &c->t_spill}) t->valid = false;
+    return PSX_OK;
+}
+
+extern "C" int32_t psx_ctx_get_timing(psx_ctx *c, psx_timing *out) {
+    if (c == nullptr || out == nullptr) return fail(PSX_EINVAL, "psx_ctx_get_timing: NULL argument");
+    memset(out, 0, sizeof(*out));
+    float *dst[4] = {&out->pack_ms, &out->check_ms, &out->adam_ms, &out->spill_ms};
+    TimedSpan *src[4] = {&c->t_pack, &c->t_check, &c->t_adam, &c->t_spill};
+    for (int i = 0; i < 4; i++) {
+        if (!src[i]->valid) continue;
+        PSX_HIP(hipEventSynchronize(src[i]->b));
+        PSX_HIP(hipEventElapsedTime(dst[i], src[i]->a, src[i]->b));
+    }
+    out->adam_elems = c->adam_elems;
+    out->spill_elems = c->spill_elems;
+    out->h2d_bytes = c->h2d_bytes;
+    out->d2h_bytes = c->d2h_bytes;
+    return PSX_OK;
+}
+
+extern "C" int32_t psx_copy_bytes(psx_ctx *c, void *dst, const void *src, uint64_t n_bytes, void *stream) {
+    if (c == nullptr) return fail(PSX_EINVAL, "psx_copy_bytes: ctx is NULL");
+    if (n_bytes == 0) return PSX_OK;
+    if (dst == nullptr || src == nullptr) return fail(PSX_EINVAL, "psx_copy_bytes: NULL pointer");
+    if (!aligned16(dst) || !aligned16(src) || n_bytes % 16 != 0)
+        return fail(PSX_EALIGN, "psx_copy_bytes: pointers and size must be multiples of 16");
+    int32_t rc = set_device_guard(c);
+    if (rc != PSX_OK) return rc;
+    PSX_HIP(launch_copy_bytes(dst, src, n_bytes, c->tune, c->n_cu, static_cast<hipStream_t>(stream)));
+    return PSX_OK;
+}
+
+// ====================================================================== pack / unpack
+
+namespace {
+
+// Cut every tensor into pieces that lie inside one chunk and emit one copy
+// segment per piece.  to_chunk selects the direction.
+int32_t build_segments(psx_ctx *c, const char *who, uint32_t dtype, const void *const *tensors,
+                       const psx_slot *slots, size_t n, const void *const *chunks, size_t n_chunks,
+                       uint64_t chunk_elems, bool to_chunk, uint64_t *n_tiles_out, uint64_t *n_elems_out) {
+    if (c == nullptr) return fail(PSX_EINVAL, "%s: ctx is NULL", who);
+    if (dtype != PSX_F16 && dtype != PSX_F32) return fail(PSX_EINVAL, "%s: dtype %u is neither PSX_F16 nor PSX_F32", who, dtype);
+    if (chunk_elems == 0) return fail(PSX_EINVAL, "%s: chunk_elems is 0", who);
+    if (n != 0 && (tensors == nullptr || slots == nullptr)) return fail(PSX_EINVAL, "%s: tensors/slots is NULL", who);
+    if (n_chunks != 0 && chunks == nullptr) return fail(PSX_EINVAL, "%s: chunks is NULL", who);
+    if (n_chunks > c->cfg.max_chunks) return fail(PSX_ECAP, "%s: %zu chunks, context holds %llu", who, n_chunks, (unsigned long long)c->cfg.max_chunks);
+    if (n > c->cfg.max_tensors) return fail(PSX_ECAP, "%s: %zu tensors, context holds %llu", who, n, (unsigned long long)c->cfg.max_tensors);
+    const uint32_t es = dtype == PSX_F16 ? 2u : 4u;
+    const uint64_t tile_elems = kCopyTileBytes / es;
+    const uint64_t total = (uint64_t)n_chunks * chunk_elems;
+    for (size_t k = 0; k < n_chunks; k++) {
+        if (chunks[k] == nullptr) return fail(PSX_EINVAL, "%s: chunk %zu is NULL", who, k);
+        if (reinterpret_cast<uintptr_t>(chunks[k]) % es) return fail(PSX_EALIGN, "%s: chunk %zu is not element-aligned", who, k);
+    }
+    c->segs.clear();
+    uint64_t tiles = 0, elems = 0;
+    for (size_t i = 0; i < n; i++) {
+        const uint64_t s = slots[i].numel;
+        if (s == 0) continue;
+        if (tensors[i] == nullptr) return fail(PSX_EINVAL, "%s: tensor %zu is NULL", who, i);
+        if (reinterpret_cast<uintptr_t>(tensors[i]) % es) return fail(PSX_EALIGN, "%s: tensor %zu is not element-aligned", who, i);
+        if (slots[i].offset > chunk_elems) return fail(PSX_EINVAL, "%s: slot %zu offset beyond the chunk", who, i);
+        const uint64_t lin = (uint64_t)slots[i].chunk * chunk_elems + slots[i].offset;
+        if (lin > total || s > total - lin)
+            return fail(PSX_EINVAL, "%s: slot %zu (chunk %u offset %llu numel %llu) runs past the chunk list", who, i,
+                        slots[i].chunk, (unsigned long long)slots[i].offset, (unsigned long long)s);
+        uint64_t done = 0;
+        while (done < s) {
+            const uint64_t p = lin + done;
+            const uint64_t ck = p / chunk_elems, off = p % chunk_elems;
+            const uint64_t take = s - done < chunk_elems - off ? s - done : chunk_elems - off;
+            const unsigned char *t = static_cast<const unsigned char *>(tensors[i]) + done * es;
+            const unsigned char *k = static_cast<const unsigned char *>(chunks[ck]) + off * es;
+            CopySeg g;
+            g.src = to_chunk ? t : k;
+            g.dst = const_cast<unsigned char *>(to_chunk ? k : t);
+            g.n = take; g.tile_begin = tiles; g.chunk = (uint32_t)ck; g.pad = 0;
+            c->segs.push_back(g);
+            tiles += (take + tile_elems - 1) / tile_elems;
+            done += take;
+        }
+        elems += s;
+    }
+    *n_tiles_out = tiles;
+    *n_elems_out = elems;
+    return PSX_OK;
+}
+
+int32_t run_copy(psx_ctx *c, Table &tbl, uint32_t dtype, uint64_t tiles, bool check, hipStream_t s) {
+    int32_t rc = set_device_guard(c);
+    if (rc != PSX_OK) return rc;
+    if (tiles == 0) return PSX_OK;
+    if (c->segs.size() > 0xFFFFFFFFull) return fail(PSX_ECAP, "too many copy segments");
+    rc = table_upload(tbl, c->segs.data(), c->segs.size() * sizeof(CopySeg), s);
+    if (rc != PSX_OK) return rc;
+    if ((rc = span_begin(c, c->t_pack, s)) != PSX_OK) return rc;
+    PSX_HIP(launch_copy(static_cast<const CopySeg *>(tbl.dev), (uint32_t)c->segs.size(), tiles,
+                        dtype == PSX_F16 ? 2u : 4u, check ? c->flags_dev : nullptr,
+                        check ? c->flags_dev + 1 : nullptr, c->tune, c->n_cu, s));
+    return span_end(c, c->t_pack, s);
+}
+
+}  // namespace
+
+extern "C" int32_t psx_pack(psx_ctx *c, uint32_t dtype, const void *const *tensors, const psx_slot *slots,
+                            size_t n, void *const *chunks, size_t n_chunks, uint64_t chunk_elems,
+                            uint32_t flags, void *stream) {
+    if (flags & ~PSX_PACK_CHECK_OVERFLOW) return fail(PSX_EINVAL, "psx_pack: unknown flags 0x%x", flags);
+    if ((flags & PSX_PACK_CHECK_OVERFLOW) && dtype != PSX_F16)
+        return fail(PSX_EINVAL, "psx_pack: PSX_PACK_CHECK_OVERFLOW needs PSX_F16");
+    uint64_t tiles = 0, elems = 0;
+    int32_t rc = build_segments(c, "psx_pack", dtype, tensors, slots, n, chunks, n_chunks, chunk_elems, true, &tiles, &elems);
+    if (rc != PSX_OK) return rc;
+    return run_copy(c, c->pack_tbl, dtype, tiles, (flags & PSX_PACK_CHECK_OVERFLOW) != 0, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int32_t psx_unpack(psx_ctx *c, uint32_t dtype, void *const *tensors, const psx_slot *slots,
+                              size_t n, const void *const *chunks, size_t n_chunks, uint64_t chunk_elems,
+                              uint32_t flags, void *stream) {
+    if (flags != 0) return fail(PSX_EINVAL, "psx_unpack: unknown flags 0x%x", flags);
+    uint64_t tiles = 0, elems = 0;
+    int32_t rc = build_segments(c, "psx_unpack", dtype, tensors, slots, n, chunks, n_chunks, chunk_elems, false, &tiles, &elems);
+    if (rc != PSX_OK) return rc;
+    return run_copy(c, c->unpack_tbl, dtype, tiles, false, static_cast<hipStream_t>(stream));
+}
+
+// ====================================================================== overflow flag
+
+extern "C" int32_t psx_overflow_reset(psx_ctx *c, void *stream) {
+    if (c == nullptr) return fail(PSX_EINVAL, "psx_overflow_reset: ctx is NULL");
+    int32_t rc = set_device_guard(c);
+    if (rc != PSX_OK) return rc;
+    PSX_HIP(launch_fill_u32(c->flags_dev, c->flags_n, 0u, static_cast<hipStream_t>(stream)));
+    return PSX_OK;
+}
+
+extern "C" int32_t psx_overflow_read(psx_ctx *c, uint32_t *per_chunk, size_t n_chunks, uint32_t *flag_out,
+                                     void *stream) {
+    if (c == nullptr) return fail(PSX_EINVAL, "psx_overflow_read: ctx is NULL");
+    if (per_chunk != nullptr && n_chunks > c->cfg.max_chunks)
+        return fail(PSX_ECAP, "psx_overflow_read: %zu chunks, context holds %llu", n_chunks, (unsigned long long)c->cfg.max_chunks);
+    int32_t rc = set_device_guard(c);
+    if (rc != PSX_OK) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const size_t cnt = 1 + (per_chunk ? n_chunks : 0);
+    PSX_HIP(hipMemcpyAsync(c->flags_host, c->flags_dev, cnt * sizeof(uint32_t), hipMemcpyDeviceToHost, s));
+    PSX_HIP(hipStreamSynchronize(s));
+    if (flag_out) *flag_out = c->flags_host[0] ? 1u : 0u;
+    if (per_chunk)
+        for (size_t k = 0; k < n_chunks; k++) per_chunk[k] = c->flags_host[1 + k] ? 1u : 0u;
+    return PSX_OK;
+}
+
+extern "C" int32_t psx_overflow_check(psx_ctx *c, const void *const *g16_chunks, const uint64_t *used,
+                                      size_t n_chunks, uint32_t *per_chunk, uint32_t *flag_out, void *stream) {
+    if (c == nullptr) return fail(PSX_EINVAL, "psx_overflow_check: ctx is NULL");
+    if (n_chunks != 0 && (g16_chunks == nullptr || used == nullptr)) return fail(PSX_EINVAL, "psx_overflow_check: NULL array");
+    if (n_chunks > c->cfg.max_chunks)
+        return fail(PSX_ECAP, "psx_overflow_check: %zu chunks, context holds %llu", n_chunks, (unsigned long long)c->cfg.max_chunks);
+    c->runs.clear();
+    uint64_t tiles = 0;
+    for (size_t k = 0; k < n_chunks; k++) {
+        if (used[k] == 0) continue;
+        if (g16_chunks[k] == nullptr) return fail(PSX_EINVAL, "psx_overflow_check: chunk %zu is NULL", k);
+        if (!aligned16(g16_chunks[k])) return fail(PSX_EALIGN, "psx_overflow_check: chunk %zu is not 16-byte aligned", k);
+        tiles += push_run(c->runs, g16_chunks[k], nullptr, nullptr, nullptr, nullptr, used[k], tiles, kCheckTileElems, (uint32_t)k);
+    }
+    int32_t rc = set_device_guard(c);
+    if (rc != PSX_OK) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    rc = table_upload(c->check_tbl, c->runs.data(), c->runs.size() * sizeof(AdamRun), s);
+    if (rc != PSX_OK) return rc;
+    PSX_HIP(launch_fill_u32(c->flags_dev, c->flags_n, 0u, s));
+    if ((rc = span_begin(c, c->t_check, s)) != PSX_OK) return rc;
+    PSX_HIP(launch_check(static_cast<const AdamRun *>(c->check_tbl.dev), (uint32_t)c->runs.size(), tiles,
+                         c->flags_dev, c->flags_dev + 1, c->tune, c->n_cu, s));
+    if ((rc = span_end(c, c->t_check, s)) != PSX_OK) return rc;
+    if (per_chunk != nullptr || flag_out != nullptr) return psx_overflow_read(c, per_chunk, n_chunks, flag_out, stream);
+    return PSX_OK;
+}
+
+// ====================================================================== Adam step
+
+namespace {
+
+int32_t prepare_scalars(const psx_adam_hyper *h, AdamScalars *s) {
+    if (!(h->loss_scale > 0.0) || !std::isfinite(h->loss_scale)) return fail(PSX_EINVAL, "psx_chunk_adam_step: loss_scale must be positive and finite");
+    if (h->step == 0) return fail(PSX_EINVAL, "psx_chunk_adam_step: step is 1-based");
+    if (!(h->beta1 >= 0.0 && h->beta1 < 1.0) || !(h->beta2 >= 0.0 && h->beta2 < 1.0))
+        return fail(PSX_EINVAL, "psx_chunk_adam_step: betas must lie in [0, 1)");
+    const double t = (double)h->step;
+    const double b1t = std::pow(h->beta1, t);
+    const double b2t = std::pow(h->beta2, t);
+    s->step_size = (float)(h->lr / (1.0 - b1t));
+    s->c2 = (float)(1.0 / std::sqrt(1.0 - b2t));
+    s->inv_scale = (float)(1.0 / h->loss_scale);
+    s->beta1 = (float)h->beta1;
+    s->beta2 = (float)h->beta2;
+    s->omb1 = (float)(1.0 - h->beta1);
+    s->omb2 = (float)(1.0 - h->beta2);
+    s->eps = (float)h->eps;
+    s->wd = (float)h->weight_decay;
+    s->decay = (float)(1.0 - h->lr * h->weight_decay);
+    s->decay_mode = s->wd == 0.0f ? 0u : (h->adamw_mode ? 2u : 1u);
+    return PSX_OK;
+}
+
+struct SpillTile {
+    size_t run;            // index into the table (its AdamRun)
+    const float *src[3];   // host sources (H2D) or NULL
+    float *stage[3];       // device targets of the H2D / sources of the D2H
+    float *dst[3];         // host targets (D2H) or NULL
+    uint64_t n;
+    bool alias;
+};
+
+}  // namespace
+
+extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size_t n_chunks,
+                                       const psx_adam_hyper *hyper, uint32_t flags, void *stream) {
+    if (c == nullptr) return fail(PSX_EINVAL, "psx_chunk_adam_step: ctx is NULL");
+    if (hyper == nullptr) return fail(PSX_EINVAL, "psx_chunk_adam_step: hyper is NULL");
+    if (n_chunks != 0 && chunks == nullptr) return fail(PSX_EINVAL, "psx_chunk_adam_step: chunks is NULL");
+    if (flags & ~(PSX_STEP_USE_FLAG | PSX_STEP_CHECK_FIRST)) return fail(PSX_EINVAL, "psx_chunk_adam_step: unknown flags 0x%x", flags);
+    if (n_chunks > c->cfg.max_chunks)
+        return fail(PSX_ECAP, "psx_chunk_adam_step: %zu chunks, context holds %llu", n_chunks, (unsigned long long)c->cfg.max_chunks);
+    AdamScalars sc;
+    int32_t rc = prepare_scalars(hyper, &sc);
+    if (rc != PSX_OK) return rc;
+    const bool check_first = (flags & PSX_STEP_CHECK_FIRST) != 0;
+    const bool use_flag = check_first || (flags & PSX_STEP_USE_FLAG) != 0;
+    const uint64_t T = c->cfg.staging_tile_elems;
+
+    // ---- validate everything before any work is enqueued
+    for (size_t k = 0; k < n_chunks; k++) {
+        const psx_chunk &ch = chunks[k];
+        if (ch.loc_in > PSX_LOC_HOST || ch.loc_out > PSX_LOC_HOST)
+            return fail(PSX_EINVAL, "psx_chunk_adam_step: chunk %zu has a bad residency (%u -> %u)", k, ch.loc_in, ch.loc_out);
+        if (ch.used == 0) continue;
+        if (ch.g16 == nullptr || ch.p16 == nullptr) return fail(PSX_EINVAL, "psx_chunk_adam_step: chunk %zu g16/p16 is NULL", k);
+        if (!aligned16(ch.g16) || !aligned16(ch.p16)) return fail(PSX_EALIGN, "psx_chunk_adam_step: chunk %zu g16/p16 not 16-byte aligned", k);
+        const bool dev_side = ch.loc_in == PSX_LOC_HBM || ch.loc_out == PSX_LOC_HBM;
+        const bool host_side = ch.loc_in == PSX_LOC_HOST || ch.loc_out == PSX_LOC_HOST;
+        if (dev_side) {
+            if (!ch.p32 || !ch.m || !ch.v) return fail(PSX_EINVAL, "psx_chunk_adam_step: chunk %zu needs device p32/m/v", k);
+            if (!aligned16(ch.p32) || !aligned16(ch.m) || !aligned16(ch.v)) return fail(PSX_EALIGN, "psx_chunk_adam_step: chunk %zu device states not 16-byte aligned", k);
+        }
+        if (host_side) {
+            if (!ch.p32_host || !ch.m_host || !ch.v_host) return fail(PSX_EINVAL, "psx_chunk_adam_step: chunk %zu needs pinned p32/m/v", k);
+            if (!aligned16(ch.p32_host) || !aligned16(ch.m_host) || !aligned16(ch.v_host)) return fail(PSX_EALIGN, "psx_chunk_adam_step: chunk %zu host states not 16-byte aligned", k);
+            if (T == 0) return fail(PSX_ENOSTAGING, "psx_chunk_adam_step: chunk %zu is host-resident but the context has no staging", k);
+        }
+    }
+    if ((rc = set_device_guard(c)) != PSX_OK) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+
+    // ---- build the descriptor table: [resident | recast | check | spill tiles]
+    const uint64_t adam_tile = adam_tile_elems(c->tune.adam_unroll);
+    const uint64_t recast_tile = adam_tile_elems(2);
+    c->runs.clear();
+    uint64_t res_tiles = 0, res_elems = 0;
+    for (size_t k = 0; k < n_chunks; k++) {
+        const psx_chunk &ch = chunks[k];
+        if (ch.used == 0 || ch.loc_in != PSX_LOC_HBM || ch.loc_out != PSX_LOC_HBM) continue;
+        res_tiles += push_run(c->runs, ch.g16, ch.p16, ch.p32, ch.m, ch.v, ch.used, res_tiles, adam_tile, (uint32_t)k);
+        res_elems += ch.used;
+    }
+    const size_t n_res = c->runs.size();
+    uint64_t recast_tiles = 0;
+    if (use_flag)
+        for (size_t k = 0; k < n_chunks; k++) {
+            const psx_chunk &ch = chunks[k];
+            if (ch.used == 0 || ch.loc_in != PSX_LOC_HBM || ch.loc_out != PSX_LOC_HBM || ch.g16 != ch.p16) continue;
+            recast_tiles += push_run(c->runs, ch.g16, ch.p16, ch.p32, ch.m, ch.v, ch.used, recast_tiles, recast_tile, (uint32_t)k);
+        }
+    const size_t n_recast = c->runs.size() - n_res;
+    uint64_t check_tiles = 0;
+    if (check_first)
+        for (size_t k = 0; k < n_chunks; k++) {
+            if (chunks[k].used == 0) continue;
+            check_tiles += push_run(c->runs, chunks[k].g16, nullptr, nullptr, nullptr, nullptr, chunks[k].used, check_tiles, kCheckTileElems, (uint32_t)k);
+        }
+    const size_t n_check = c->runs.size() - n_res - n_recast;
+
+    std::vector<SpillTile> tiles;
+    uint64_t spill_elems = 0, h2d_bytes = 0, d2h_bytes = 0;
+    uint64_t slot_counter = 0;
+    for (size_t k = 0; k < n_chunks; k++) {
+        const psx_chunk &ch = chunks[k];
+        if (ch.used == 0 || (ch.loc_in == PSX_LOC_HBM && ch.loc_out == PSX_LOC_HBM)) continue;
+        const bool in_host = ch.loc_in == PSX_LOC_HOST, out_host = ch.loc_out == PSX_LOC_HOST;
+        spill_elems += ch.used;
+        for (uint64_t off = 0; off < ch.used; off += T) {
+            const uint64_t n = ch.used - off < T ? ch.used - off : T;
+            SpillTile t{};
+            t.n = n;
+            t.alias = ch.g16 == ch.p16;
+            float *dev[3];
+            if (in_host && out_host) {
+                const uint64_t slot = slot_counter % c->cfg.staging_slots;
+                for (int j = 0; j < 3; j++) dev[j] = c->staging + ((size_t)slot * 3 + j) * T;
+            } else {
+                dev[0] = static_cast<float *>(ch.p32) + off;
+                dev[1] = static_cast<float *>(ch.m) + off;
+                dev[2] = static_cast<float *>(ch.v) + off;
+            }
+            slot_counter++;
+            const float *hs[3] = {static_cast<const float *>(ch.p32_host), static_cast<const float *>(ch.m_host), static_cast<const float *>(ch.v_host)};
+            for (int j = 0; j < 3; j++) {
+                t.stage[j] = dev[j];
+                t.src[j] = in_host ? hs[j] + off : nullptr;
+                t.dst[j] = out_host ? const_cast<float *>(hs[j]) + off : nullptr;
+            }
+            if (in_host) h2d_bytes += 3 * n * sizeof(float);
+            if (out_host) d2h_bytes += 3 * n * sizeof(float);
+            t.run = c->runs.size();
+            push_run(c->runs, static_cast<const uint16_t *>(ch.g16) + off, static_cast<uint16_t *>(ch.p16) + off,
+                     dev[0], dev[1], dev[2], n, 0, adam_tile, (uint32_t)k);
+            tiles.push_back(t);
+        }
+    }
+    if (c->runs.size() > 0xFFFFFFFFull) return fail(PSX_ECAP, "psx_chunk_adam_step: too many runs");
+    if ((rc = table_upload(c->adam_tbl, c->runs.data(), c->runs.size() * sizeof(AdamRun), s)) != PSX_OK) return rc;
+    const AdamRun *tbl = static_cast<const AdamRun *>(c->adam_tbl.dev);
+    const uint32_t *flag = use_flag ? c->flags_dev : nullptr;
+
+    // ---- copy streams may start once earlier work on the caller's stream is done
+    if (!tiles.empty()) {
+        PSX_HIP(hipEventRecord(c->ev_entry, s));
+        PSX_HIP(hipStreamWaitEvent(c->h2d, c->ev_entry, 0));
+        PSX_HIP(hipStreamWaitEvent(c->d2h, c->ev_entry, 0));
+        c->t_spill.valid = false;
+        if (c->prof) PSX_HIP(hipEventRecord(c->t_spill.a, c->h2d));
+    }
+
+    // ---- overflow check over every gradient chunk
+    if (check_first) {
+        PSX_HIP(launch_fill_u32(c->flags_dev, c->flags_n, 0u, s));
+        if ((rc = span_begin(c, c->t_check, s)) != PSX_OK) return rc;
+        PSX_HIP(launch_check(tbl + n_res + n_recast, (uint32_t)n_check, check_tiles, c->flags_dev, c->flags_dev + 1, c->tune, c->n_cu, s));
+        if ((rc = span_end(c, c->t_check, s)) != PSX_OK) return rc;
+    }
+
+    // ---- HBM-resident chunks: one launch over all of them
+    c->adam_elems = res_elems;
+    c->t_adam.valid = false;
+    if (res_tiles != 0) {
+        if ((rc = span_begin(c, c->t_adam, s)) != PSX_OK) return rc;
+        PSX_HIP(launch_adam(tbl, (uint32_t)n_res, res_tiles, sc, flag, c->tune, c->n_cu, s));
+        if ((rc = span_end(c, c->t_adam, s)) != PSX_OK) return rc;
+        if (n_recast != 0)
+            PSX_HIP(launch_recast_if_flag(tbl + n_res, (uint32_t)n_recast, recast_tiles, flag, c->tune, c->n_cu, s));
+    }
+
+    // ---- chunks with a host side: H2D (copy stream) -> update (caller's stream) -> D2H (copy stream)
+    c->spill_elems = spill_elems; c->h2d_bytes = h2d_bytes; c->d2h_bytes = d2h_bytes;
+    const size_t ring = c->ev_k.size();
+    bool any_h2d = false, any_d2h = false;
+    for (size_t i = 0; i < tiles.size(); i++) {
+        const SpillTile &t = tiles[i];
+        const size_t e = i % ring;
+        const size_t bytes = t.n * sizeof(float);
+        if (t.src[0] != nullptr) {
+            if (i >= ring) PSX_HIP(hipStreamWaitEvent(c->h2d, c->ev_free[e], 0));   // staging slot drained
+            for (int j = 0; j < 3; j++)
+                PSX_HIP(hipMemcpyAsync(t.stage[j], t.src[j], bytes, hipMemcpyHostToDevice, c->h2d));
+            PSX_HIP(hipEventRecord(c->ev_h2d[e], c->h2d));
+            PSX_HIP(hipStreamWaitEvent(s, c->ev_h2d[e], 0));
+            any_h2d = true;
+        }
+        Tuning tn = c->tune;
+        PSX_HIP(launch_adam(tbl + t.run, 1u, (t.n + adam_tile - 1) / adam_tile, sc, flag, tn, c->n_cu, s));
+        if (use_flag && t.alias)
+            PSX_HIP(launch_recast_if_flag(tbl + t.run, 1u, (t.n + recast_tile - 1) / recast_tile, flag, tn, c->n_cu, s));
+        if (t.dst[0] != nullptr) {
+            PSX_HIP(hipEventRecord(c->ev_k[e], s));
+            PSX_HIP(hipStreamWaitEvent(c->d2h, c->ev_k[e], 0));
+            for (int j = 0; j < 3; j++)
+                PSX_HIP(hipMemcpyAsync(t.dst[j], t.stage[j], bytes, hipMemcpyDeviceToHost, c->d2h));
+            PSX_HIP(hipEventRecord(c->ev_free[e], c->d2h));
+            any_d2h = true;
+        } else {
+            PSX_HIP(hipEventRecord(c->ev_free[e], s));
+        }
+    }
+    if (!tiles.empty()) {
+        if (any_h2d) { PSX_HIP(hipEventRecord(c->ev_h2d_end, c->h2d)); PSX_HIP(hipStreamWaitEvent(s, c->ev_h2d_end, 0)); }
+        if (any_d2h) { PSX_HIP(hipEventRecord(c->ev_d2h_end, c->d2h)); PSX_HIP(hipStreamWaitEvent(s, c->ev_d2h_end, 0)); }
+        if (c->prof) { PSX_HIP(hipEventRecord(c->t_spill.b, s)); c->t_spill.valid = true; }
+    }
+    return PSX_OK;
+}

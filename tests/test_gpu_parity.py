@@ -1,0 +1,389 @@
+"""GPU parity: the HIP path, called through the C ABI, against the scalar CPU
+oracle on the same seeded inputs.  Bit-exact for layout, pack/unpack, flags and
+the fp16 re-cast; p/m/v within 2 ulp (0 expected: same operations, same order,
+IEEE-correct on both sides).  The oracle runs free on its own copy of the
+seeded inputs: nothing the HIP path produced is ever fed to it."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2108_05818_amd import psx
+from paper_2108_05818_amd import workloads as W
+
+from gpu_util import DEV, SENT16, SENT32, ChunkLists, bits16, bits32, f32, from_bits16, sent16, sent32
+
+pytestmark = pytest.mark.gpu
+
+H, G = psx.PSX_LOC_HOST, psx.PSX_LOC_HBM
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = psx.psx_ctx_create(max_chunks=512, max_tensors=8192, staging_tile_elems=4096, staging_slots=3)
+    yield c
+    psx.psx_ctx_destroy(c)
+
+
+def fill_state(cl, seed, loss_scale, zero_mv=True):
+    for k in range(cl.n):
+        u = cl.used[k]
+        if u == 0:
+            continue
+        cl.set("p32", k, W.params_np(u, seed + 10 * k))
+        if zero_mv:
+            cl.set("m", k, np.zeros(u, np.float32))
+            cl.set("v", k, np.zeros(u, np.float32))
+        else:
+            cl.set("m", k, W.params_np(u, seed + 10 * k + 1) * np.float32(0.05))
+            cl.set("v", k, np.abs(W.params_np(u, seed + 10 * k + 2)) * np.float32(1e-4))
+        cl.set("g16", k, W.grads_f16_np(u, seed + 10 * k + 3, loss_scale))
+
+
+def check_recast_of_own_params(orc, cl):
+    """p16 must be exactly the fp16 (round to nearest even) of the GPU's own fp32 params."""
+    for k in range(cl.n):
+        u = cl.used[k]
+        assert np.array_equal(bits16(cl.p16[k])[:u], orc.f32_to_f16(f32(cl.p32[k])[:u])), f"chunk {k}"
+
+
+# ---------------------------------------------------------------------------------- config 1, end to end
+
+@pytest.mark.parametrize("alias", [False, True])
+def test_config1_tiny_gpt_ten_steps(orc, ctx, alias):
+    w = W.config1_tiny()
+    slots, used = psx.psx_chunk_layout(w.numel, w.chunk_elems)
+    o_slots, o_used = orc.chunk_layout(w.numel, w.chunk_elems)
+    assert used == [int(u) for u in o_used]
+    nch, Cn = len(used), w.chunk_elems
+    cl = ChunkLists(used, Cn, alias=alias)
+
+    # params: fp32 tensors packed into the p32 list on both sides; m = v = 0
+    p_np = [W.params_np(s, w.seed + i) for i, s in enumerate(w.numel)]
+    psx.psx_pack(ctx, psx.PSX_F32, [torch.from_numpy(a).to(DEV) for a in p_np], slots, cl.p32, Cn)
+    orc.pack(p_np, o_slots, cl.np["p32"], Cn)
+    for k in range(nch):
+        cl.set("m", k, np.zeros(used[k], np.float32))
+        cl.set("v", k, np.zeros(used[k], np.float32))
+    cl.compare("after param pack")
+
+    scaler = psx.make_scaler(w.loss_scale, w.growth_interval)
+    o_scaler = orc.scaler(w.loss_scale, w.growth_interval)
+    worst = 0.0
+    for step in range(w.steps):
+        g_np = [W.grads_f16_np(s, w.seed + 1000 * (step + 1) + i, scaler.scale) for i, s in enumerate(w.numel)]
+        psx.psx_pack(ctx, psx.PSX_F16, [from_bits16(a) for a in g_np], slots, cl.g16, Cn)
+        orc.pack(g_np, o_slots, cl.np["g16"], Cn)
+        for k in range(nch):
+            assert bits16(cl.g16[k]).tobytes() == cl.np["g16"][k].tobytes()
+        flag, per = psx.psx_overflow_check(ctx, cl.g16, used)
+        o_flag, o_per = orc.overflow_check(cl.np["g16"], np.array(used, np.uint64))
+        assert (flag, per) == (o_flag, list(o_per)) == (0, [0] * nch)
+        hp = dict(lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps, weight_decay=w.weight_decay,
+                  adamw_mode=w.adamw_mode, step=scaler.step, loss_scale=scaler.scale)
+        psx.psx_chunk_adam_step(ctx, psx.make_chunks(cl.specs()), psx.make_hyper(**hp), psx.PSX_STEP_USE_FLAG)
+        torch.cuda.synchronize()
+        assert cl.oracle_step(orc, orc.hyper(**hp)) == 0
+        worst = max(worst, cl.compare(f"step {step}"))
+        check_recast_of_own_params(orc, cl)
+        psx.psx_loss_scale_update(scaler, flag)
+        orc.scaler_update(o_scaler, o_flag)
+        assert (scaler.scale, scaler.step) == (o_scaler.scale, o_scaler.step)
+    print(f"config1 alias={alias}: worst error over {w.steps} free-running steps: {worst} ulp")
+    # unpack the fp16 params back into tensors
+    out = [torch.zeros(s, dtype=torch.float16, device=DEV) for s in w.numel]
+    psx.psx_unpack(ctx, psx.PSX_F16, out, slots, cl.p16, Cn)
+    o_out = [np.zeros(s, np.uint16) for s in w.numel]
+    orc.unpack(o_out, o_slots, cl.np["p16"], Cn)
+    torch.cuda.synchronize()
+    for a, b in zip(out, o_out):
+        assert bits16(a).tobytes() == b.tobytes()
+
+
+# ---------------------------------------------------------------------------------- pack / unpack
+
+@pytest.mark.parametrize("dtype", [psx.PSX_F16, psx.PSX_F32])
+def test_pack_unpack_ragged_unaligned(orc, ctx, dtype):
+    rng = np.random.default_rng(77)
+    Cn = 20000
+    numel = [1, 3, 0, 7, 8, 9, 8191, 8193, 1, 16384, 2, 45001, 5, 19999, 20000, 1, 61234, 33, 4095, 1, 1, 12345, 8192]
+    numel += [int(x) for x in rng.integers(0, 3000, size=150)]
+    npd, ipd, sent = (np.uint16, np.int16, SENT16) if dtype == psx.PSX_F16 else (np.uint32, np.int32, SENT32)
+    slots, used = psx.psx_chunk_layout(numel, Cn)
+    o_slots, o_used = orc.chunk_layout(numel, Cn)
+    nch = len(used)
+    # tensors carved at odd element offsets out of one buffer, so sources are misaligned in every way
+    gaps = [int(x) for x in rng.integers(0, 3, size=len(numel))]
+    total = sum(numel) + sum(gaps) + 16
+    big = rng.integers(0, np.iinfo(npd).max, size=total, dtype=np.uint64).astype(npd)
+    big_t = torch.from_numpy(big.view(ipd)).to(DEV)
+    t_np, t_dev, pos = [], [], 1
+    for s, gap in zip(numel, gaps):
+        t_np.append(np.ascontiguousarray(big[pos:pos + s]))
+        t_dev.append(big_t[pos:pos + s])
+        pos += s + gap
+    chunks = [torch.from_numpy(np.full(Cn, sent, npd).view(ipd)).to(DEV) for _ in range(nch)]
+    o_chunks = [np.full(Cn, sent, npd) for _ in range(nch)]
+    psx.psx_pack(ctx, dtype, t_dev, slots, chunks, Cn)
+    orc.pack(t_np, o_slots, o_chunks, Cn)
+    torch.cuda.synchronize()
+    for k in range(nch):
+        assert chunks[k].cpu().numpy().view(npd).tobytes() == o_chunks[k].tobytes(), f"chunk {k}"
+    # unpack into fresh, equally misaligned tensors; nothing outside them may be written
+    out_big = torch.zeros_like(big_t)
+    outs, pos, mask = [], 1, np.ones(total, bool)
+    for s, gap in zip(numel, gaps):
+        outs.append(out_big[pos:pos + s])
+        mask[pos:pos + s] = False
+        pos += s + gap
+    psx.psx_unpack(ctx, dtype, outs, slots, chunks, Cn)
+    torch.cuda.synchronize()
+    for a, b in zip(outs, t_np):
+        assert a.cpu().numpy().view(npd).tobytes() == b.tobytes()
+    assert not out_big.cpu().numpy()[mask].any()
+
+
+def test_pack_with_fused_overflow_check(orc, ctx):
+    Cn = 30000
+    numel = [1, 17, 29999, 30000, 5, 70001, 12, 8192, 1]
+    slots, used = psx.psx_chunk_layout(numel, Cn)
+    o_slots, _ = orc.chunk_layout(numel, Cn)
+    nch = len(used)
+    base = [W.grads_f16_np(s, 500 + i, 1024.0) for i, s in enumerate(numel)]
+    cases = [None, (0, 0), (1, 16), (2, 29998), (5, 70000), (5, 31000), (8, 0), (6, 11)]
+    for case in cases:
+        g_np = [a.copy() for a in base]
+        if case is not None:
+            g_np[case[0]][case[1]] = 0x7C00 if case[1] % 2 == 0 else 0xFE01
+        chunks = [from_bits16(np.full(Cn, 0x7C00, np.uint16)) for _ in range(nch)]     # inf in the padding
+        o_chunks = [np.full(Cn, 0x7C00, np.uint16) for _ in range(nch)]
+        psx.psx_overflow_reset(ctx)
+        psx.psx_pack(ctx, psx.PSX_F16, [from_bits16(a) for a in g_np], slots, chunks, Cn,
+                     flags=psx.PSX_PACK_CHECK_OVERFLOW)
+        flag, per = psx.psx_overflow_read(ctx, nch)
+        orc.pack(g_np, o_slots, o_chunks, Cn)
+        o_flag, o_per = orc.overflow_check(o_chunks, np.array(used, np.uint64))
+        assert (flag, per) == (o_flag, list(o_per)), case
+        assert flag == (0 if case is None else 1)
+        for k in range(nch):
+            assert bits16(chunks[k]).tobytes() == o_chunks[k].tobytes()
+
+
+# ---------------------------------------------------------------------------------- overflow check
+
+def test_overflow_check_positions(orc, ctx):
+    Cn = 3 * 8192 + 100
+    used = [Cn, 8192, 8193, 1, 0, 16391, 7]
+    nch = len(used)
+    base = [W.grads_f16_np(Cn, 900 + k, 65536.0) for k in range(nch)]
+    for b in base:
+        b[(b & 0x7C00) == 0x7C00] = 0x7BFF
+    cases = [None]
+    for k in range(nch):
+        for pos in (0, used[k] - 1, used[k] // 2, used[k], Cn - 1):      # the last two lie in the padding
+            if 0 <= pos < Cn:
+                cases.append((k, pos))
+    specials = W.specials_f16()
+    for i, case in enumerate(cases):
+        g = [b.copy() for b in base]
+        if case is not None:
+            g[case[0]][case[1]] = specials[i % len(specials)]
+        flag, per = psx.psx_overflow_check(ctx, [from_bits16(a) for a in g], used)
+        o_flag, o_per = orc.overflow_check(g, np.array(used, np.uint64))
+        assert (flag, per) == (o_flag, list(o_per)), case
+        if case is not None:
+            assert flag == int(case[1] < used[case[0]])
+    # max finite and subnormals never trigger
+    g = [np.tile(np.array([0x7BFF, 0xFBFF, 0x0001, 0x83FF], np.uint16), Cn // 4 + 1)[:Cn] for _ in range(nch)]
+    flag, per = psx.psx_overflow_check(ctx, [from_bits16(a) for a in g], used)
+    assert flag == 0 and not any(per)
+
+
+# ---------------------------------------------------------------------------------- Adam arithmetic
+
+RAGGED_USED = [1, 3, 4, 5, 1023, 1024, 1025, 2047, 2049, 4096, 4097, 8191, 12289, 0, 20000]
+
+
+@pytest.mark.parametrize("wd,adamw", [(0.0, 0), (0.01, 0), (0.01, 1)])
+@pytest.mark.parametrize("unroll,nt", [(1, 1), (2, 0), (2, 1), (4, 1)])
+def test_adam_matches_oracle_over_ragged_chunks(orc, ctx, wd, adamw, unroll, nt):
+    psx.psx_ctx_set_tuning(ctx, psx.PSX_TUNE_ADAM_UNROLL, unroll)
+    psx.psx_ctx_set_tuning(ctx, psx.PSX_TUNE_NONTEMPORAL, nt)
+    try:
+        Cn = 20000
+        cl = ChunkLists(RAGGED_USED, Cn)
+        fill_state(cl, 4000, 65536.0, zero_mv=False)
+        # a few special gradients: zeros, fp16 subnormals, largest finite values
+        cl.set("g16", 14, np.array([0, 0x8000, 1, 0x8001, 0x03FF, 0x7BFF, 0xFBFF, 0x0400], np.uint16))
+        worst = 0.0
+        for t in (1, 2, 7):
+            hp = dict(lr=1e-3, weight_decay=wd, adamw_mode=adamw, step=t, loss_scale=65536.0)
+            psx.psx_chunk_adam_step(ctx, psx.make_chunks(cl.specs()), psx.make_hyper(**hp))
+            torch.cuda.synchronize()
+            assert cl.oracle_step(orc, orc.hyper(**hp)) == 0
+            worst = max(worst, cl.compare(f"t={t}"))
+            check_recast_of_own_params(orc, cl)
+        assert worst == 0.0, f"expected bit-exact, got {worst} ulp"
+    finally:
+        psx.psx_ctx_set_tuning(ctx, psx.PSX_TUNE_ADAM_UNROLL, 2)
+        psx.psx_ctx_set_tuning(ctx, psx.PSX_TUNE_NONTEMPORAL, 1)
+
+
+def test_adam_closed_forms_on_gpu(ctx):
+    """The closed forms of Kingma & Ba's algorithm, evaluated on the HIP path itself."""
+    n = 4096 + 3
+    cl = ChunkLists([n], 8192)
+    g = np.random.default_rng(1).standard_normal(n).astype(np.float32) * 1e-3
+    g16 = (g * 1024).astype(np.float16)
+    cl.set("g16", 0, g16.view(np.uint16))
+    cl.set("p32", 0, np.full(n, 0.5, np.float32))
+    cl.set("m", 0, np.zeros(n, np.float32))
+    cl.set("v", 0, np.zeros(n, np.float32))
+    psx.psx_chunk_adam_step(ctx, psx.make_chunks(cl.specs()), psx.make_hyper(lr=1e-3, step=1, loss_scale=1024.0))
+    gd = g16.astype(np.float64) / 1024
+    want = 0.5 - 1e-3 * gd / (np.abs(gd) + 1e-8)
+    assert np.allclose(f32(cl.p32[0])[:n], want, rtol=0, atol=1e-7)
+    # zero gradient from zero state: nothing moves
+    cl2 = ChunkLists([n], 8192)
+    cl2.set("g16", 0, np.zeros(n, np.uint16))
+    cl2.set("p32", 0, W.params_np(n, 5))
+    cl2.set("m", 0, np.zeros(n, np.float32))
+    cl2.set("v", 0, np.zeros(n, np.float32))
+    psx.psx_chunk_adam_step(ctx, psx.make_chunks(cl2.specs()), psx.make_hyper(lr=1e-3, step=1, loss_scale=1024.0))
+    assert bits32(cl2.p32[0]).tobytes() == cl2.np["p32"][0].view(np.uint32).tobytes()
+    assert not f32(cl2.m[0])[:n].any() and not f32(cl2.v[0])[:n].any()
+
+
+def test_fp16_recast_is_round_to_nearest_even(orc, ctx):
+    """Every fp16 tie, its fp32 neighbours, boundaries and subnormals through the kernel's conversion."""
+    h = np.arange(0, 0x7C00, dtype=np.uint32).astype(np.uint16)
+    lo = h.view(np.float16).astype(np.float64)
+    hi = (h + 1).astype(np.uint16).view(np.float16).astype(np.float64)
+    hi[-1] = 65536.0
+    mid = ((lo + hi) / 2).astype(np.float32)
+    vals = np.concatenate([mid, np.nextafter(mid, np.float32(np.inf)), np.nextafter(mid, np.float32(-np.inf)),
+                           lo.astype(np.float32), W.params_np(50000, 6),
+                           np.array([0, 65504, 65519.99, 65520, 65536, 1e30, np.inf, 2.0 ** -24, 2.0 ** -25,
+                                     2.0 ** -26, 1e-45, 1.17549435e-38, 3.4e38], np.float32)])
+    vals = np.concatenate([vals, -vals]).astype(np.float32)
+    n = vals.size
+    cl = ChunkLists([n], n + 5, alias=True)
+    cl.set("p32", 0, vals)
+    cl.set("m", 0, np.zeros(n, np.float32))
+    cl.set("v", 0, np.zeros(n, np.float32))
+    g = np.zeros(n, np.uint16)
+    g[7] = 0x7C00                        # overflow: the step is skipped and the aliased chunk re-cast
+    cl.set("g16", 0, g)
+    hp = dict(step=1, loss_scale=1.0)
+    psx.psx_chunk_adam_step(ctx, psx.make_chunks(cl.specs()), psx.make_hyper(**hp), psx.PSX_STEP_CHECK_FIRST)
+    flag, _ = psx.psx_overflow_read(ctx)
+    assert flag == 1 == cl.oracle_step(orc, orc.hyper(**hp))
+    assert cl.compare("recast") == 0.0
+    with np.errstate(over="ignore"):
+        assert np.array_equal(bits16(cl.p16[0])[:n], vals.astype(np.float16).view(np.uint16))
+
+
+# ---------------------------------------------------------------------------------- skip semantics
+
+@pytest.mark.parametrize("alias", [False, True])
+def test_overflow_skips_the_whole_step(orc, ctx, alias):
+    used = [20000, 12289, 1, 4097]
+    Cn = 20000
+    for (k, pos, special) in [(0, 0, 0x7C00), (1, 12288, 0xFC00), (2, 0, 0x7E00), (3, 4096, 0x7D01)]:
+        cl = ChunkLists(used, Cn, alias=alias)
+        fill_state(cl, 7000, 1024.0, zero_mv=False)
+        cl.set("g16", k, np.array([special], np.uint16), at=pos)
+        before = [bits32(x).copy() for x in cl.p32 + cl.m + cl.v]
+        hp = dict(lr=1e-3, weight_decay=0.01, step=5, loss_scale=1024.0)
+        psx.psx_chunk_adam_step(ctx, psx.make_chunks(cl.specs()), psx.make_hyper(**hp), psx.PSX_STEP_CHECK_FIRST)
+        flag, per = psx.psx_overflow_read(ctx, len(used))
+        assert flag == 1 == cl.oracle_step(orc, orc.hyper(**hp))
+        assert per[k] == 1 and sum(per) == 1
+        assert cl.compare("skipped") == 0.0
+        for a, b in zip(cl.p32 + cl.m + cl.v, before):       # fp32 states keep their bits
+            assert bits32(a).tobytes() == b.tobytes()
+    # a special value in the padding does not skip
+    cl = ChunkLists(used, Cn, alias=False)
+    fill_state(cl, 7100, 1024.0)
+    cl.set("g16", 1, np.array([0x7C00], np.uint16), at=12289)
+    hp = dict(step=1, loss_scale=1024.0)
+    psx.psx_chunk_adam_step(ctx, psx.make_chunks(cl.specs()), psx.make_hyper(**hp), psx.PSX_STEP_CHECK_FIRST)
+    flag, _ = psx.psx_overflow_read(ctx)
+    assert flag == 0 == cl.oracle_step(orc, orc.hyper(**hp))
+    assert cl.compare("padding special") == 0.0
+
+
+# ---------------------------------------------------------------------------------- host-resident chunks
+
+@pytest.mark.parametrize("slots", [2, 3])
+@pytest.mark.parametrize("alias", [False, True])
+def test_host_resident_chunks_stream_through_staging(orc, alias, slots):
+    ctx = psx.psx_ctx_create(max_chunks=64, max_tensors=16, staging_tile_elems=4096, staging_slots=slots)
+    try:
+        used = [20000, 4096, 12289, 1, 4097, 0, 16384, 9000]
+        loc = [(G, G), (H, H), (H, H), (H, H), (H, G), (H, H), (G, H), (H, H)]
+        Cn = 20000
+        cl = ChunkLists(used, Cn, alias=alias)
+        fill_state(cl, 8000, 65536.0, zero_mv=False)
+        host = []
+        for k in range(cl.n):
+            hs = [torch.from_numpy(sent32(Cn)).pin_memory() for _ in range(3)]
+            if loc[k][0] == H:          # the state starts on the host; the device copy is garbage
+                for hbuf, name in zip(hs, ("p32", "m", "v")):
+                    hbuf.copy_(torch.from_numpy(cl.np[name][k]))
+                    if loc[k][1] == H:
+                        getattr(cl, name)[k].view(torch.int32).fill_(0x0BADBEEF)
+            host.append(hs)
+        for t in (1, 2, 3):
+            hp = dict(lr=1e-3, weight_decay=0.01, step=t, loss_scale=65536.0)
+            psx.psx_chunk_adam_step(ctx, psx.make_chunks(cl.specs(loc=loc, host=host)), psx.make_hyper(**hp),
+                                    psx.PSX_STEP_CHECK_FIRST)
+            torch.cuda.synchronize()
+            assert cl.oracle_step(orc, orc.hyper(**hp)) == 0
+            where = [host[k] if loc[k][1] == H else None for k in range(cl.n)]
+            assert cl.compare(f"t={t}", where=where) == 0.0
+            tm = psx.psx_ctx_get_timing(ctx)
+            assert tm.spill_elems == sum(u for u, l in zip(used, loc) if l != (G, G))
+            assert tm.h2d_bytes == 12 * sum(u for u, l in zip(used, loc) if l[0] == H)
+            assert tm.d2h_bytes == 12 * sum(u for u, l in zip(used, loc) if l[1] == H)
+            # the next step finds the state where this one left it
+            loc = [(b, b) for (_, b) in loc]
+            for k in range(cl.n):
+                cl.set("g16", k, W.grads_f16_np(used[k], 8500 + 10 * k + t, 65536.0))
+    finally:
+        psx.psx_ctx_destroy(ctx)
+
+
+def test_bad_arguments_touch_nothing():
+    ctx = psx.psx_ctx_create(max_chunks=4, max_tensors=4)
+    try:
+        cl = ChunkLists([64], 64)
+        fill_state(cl, 1, 1.0)
+        hs = [torch.zeros(64).pin_memory() for _ in range(3)]
+        spec = cl.specs(loc=[(H, H)], host=[hs])
+        with pytest.raises(psx.PsxError) as e:
+            psx.psx_chunk_adam_step(ctx, psx.make_chunks(spec), psx.make_hyper())
+        assert e.value.code == psx.PSX_ENOSTAGING
+        with pytest.raises(psx.PsxError) as e:      # misaligned chunk base
+            bad = cl.specs()
+            bad[0]["p32"] = cl.p32[0].data_ptr() + 4
+            psx.psx_chunk_adam_step(ctx, psx.make_chunks(bad), psx.make_hyper())
+        assert e.value.code == psx.PSX_EALIGN
+        with pytest.raises(psx.PsxError) as e:      # more chunks than the context holds
+            psx.psx_chunk_adam_step(ctx, psx.make_chunks(cl.specs() * 5), psx.make_hyper())
+        assert e.value.code == psx.PSX_ECAP
+        with pytest.raises(psx.PsxError) as e:
+            psx.psx_chunk_adam_step(ctx, psx.make_chunks(cl.specs()), psx.make_hyper(step=0))
+        assert e.value.code == psx.PSX_EINVAL
+        slots, used = psx.psx_chunk_layout([64], 64)
+        with pytest.raises(psx.PsxError) as e:      # slot running past the chunk list
+            slots[0].numel = 65
+            psx.psx_pack(ctx, psx.PSX_F32, [cl.m[0]], slots, [cl.p32[0]], 64)
+        assert e.value.code == psx.PSX_EINVAL
+        with pytest.raises(psx.PsxError) as e:      # fused check is for fp16 only
+            slots[0].numel = 64
+            psx.psx_pack(ctx, psx.PSX_F32, [cl.m[0]], slots, [cl.p32[0]], 64, flags=psx.PSX_PACK_CHECK_OVERFLOW)
+        assert e.value.code == psx.PSX_EINVAL
+        torch.cuda.synchronize()
+        assert cl.compare("after refused calls") == 0.0       # nothing was touched
+    finally:
+        psx.psx_ctx_destroy(ctx)

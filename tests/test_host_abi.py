@@ -1,0 +1,93 @@
+"""CPU-side tests of the C-ABI library: it loads, exports every symbol the
+header declares, and its host-only entry points (layout, loss scaler, argument
+validation) agree with the oracle.  No GPU work is issued here."""
+import ctypes as C
+import itertools
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2108_05818_amd import psx
+from paper_2108_05818_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "psx.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(psx_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(psx.EXPORTS)
+    L = psx.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+
+
+def _same_layout(orc, numel, C_, flags=0):
+    o_slots, o_used = orc.chunk_layout(numel, C_, strict=bool(flags & psx.PSX_LAYOUT_STRICT))
+    slots, used = psx.psx_chunk_layout(numel, C_, flags)
+    assert used == [int(u) for u in o_used]
+    for i in range(len(numel)):
+        assert (slots[i].chunk, slots[i].offset, slots[i].numel) == \
+               (o_slots[i].chunk, o_slots[i].offset, o_slots[i].numel), (numel, C_, i)
+
+
+def test_layout_matches_oracle_exhaustive_small(orc):
+    for n in range(0, 5):
+        for numel in itertools.product([0, 1, 2, 3, 5, 8, 13], repeat=n):
+            for C_ in (1, 2, 3, 4, 5, 8, 16):
+                _same_layout(orc, list(numel), C_)
+
+
+def test_layout_matches_oracle_random_and_configs(orc):
+    rng = np.random.default_rng(3)
+    for _ in range(300):
+        n = int(rng.integers(1, 60))
+        C_ = int(rng.integers(1, 100))
+        _same_layout(orc, [int(x) for x in rng.integers(0, 3 * C_, size=n)], C_)
+    for w in (W.config1_tiny(), W.config2_gpt1b(), W.config3_ragged(), W.config4_gpt12b(), W.config5_gpt20b()):
+        _same_layout(orc, w.numel, w.chunk_elems)
+    w = W.config1_tiny()
+    _same_layout(orc, w.numel, w.chunk_elems, psx.PSX_LAYOUT_STRICT)
+
+
+def test_layout_errors():
+    with pytest.raises(psx.PsxError) as e:
+        psx.psx_chunk_layout([4, 9, 2], 8, psx.PSX_LAYOUT_STRICT)
+    assert e.value.code == psx.PSX_ETOOLARGE and "tensor 1" in str(e.value)
+    with pytest.raises(psx.PsxError) as e:
+        psx.psx_chunk_layout([1], 0)
+    assert e.value.code == psx.PSX_EINVAL
+    # used[] too short
+    L = psx.lib()
+    numel = (C.c_uint64 * 3)(8, 8, 8)
+    used = (C.c_uint64 * 2)(7, 7)
+    nch = C.c_size_t(0)
+    assert L.psx_chunk_layout(numel, 3, 8, 0, None, used, 2, C.byref(nch)) == psx.PSX_ECAP
+    assert list(used) == [7, 7]                      # nothing written on error
+    assert L.psx_chunk_layout(numel, 3, 8, 0x80, None, None, 0, C.byref(nch)) == psx.PSX_EINVAL
+    assert L.psx_chunk_layout(None, 3, 8, 0, None, None, 0, C.byref(nch)) == psx.PSX_EINVAL
+
+
+def test_scaler_matches_oracle(orc):
+    rng = np.random.default_rng(12)
+    for gi in (1, 2, 3, 50):
+        a = psx.make_scaler(65536.0, gi)
+        b = orc.scaler(65536.0, gi)
+        for ov in rng.random(400) < 0.15:
+            psx.psx_loss_scale_update(a, ov)
+            orc.scaler_update(b, ov)
+            assert (a.scale, a.good_steps, a.step) == (b.scale, b.good_steps, b.step)
+
+
+def test_null_arguments_are_errors_not_crashes():
+    L = psx.lib()
+    assert L.psx_loss_scale_update(None, 0) == psx.PSX_EINVAL
+    assert L.psx_ctx_create(None, None) == psx.PSX_EINVAL
+    assert L.psx_ctx_destroy(None) == psx.PSX_OK
+    assert L.psx_pack(None, 1, None, None, 0, None, 0, 8, 0, None) == psx.PSX_EINVAL
+    assert L.psx_overflow_check(None, None, None, 0, None, None, None) == psx.PSX_EINVAL
+    assert L.psx_chunk_adam_step(None, None, 0, None, 0, None) == psx.PSX_EINVAL
+    assert b"ctx is NULL" in L.psx_last_error()
