@@ -1,0 +1,283 @@
+#!/usr/bin/env python3
+"""Benchmark of the chunked mixed-precision Adam path on one MI355X.
+
+A "step" is one pass of the whole hot path over the synthetic GPT-shaped
+parameter set, every part of it in the HIP library behind include/psx.h:
+  psx_chunk_layout (host)  ->  psx_pack of the fp16 gradients into their chunk
+  slots  ->  overflow check over all gradient chunks  ->  fused Adam over the
+  chunk list (fp32 p/m/v updated, fp16 params written)  ->  psx_unpack of the
+  fp16 params  ->  flag read-back (4 bytes, synchronises) and loss-scale update.
+Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps 20] [--warmup 3] [--workload gpt1b|tiny|gpt12b]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+ADAM_BYTES_PER_ELEM = 28       # read g16 2 + p,m,v 12; write p,m,v 12 + p16 2
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="gpt1b", choices=["gpt1b", "tiny", "gpt12b"])
+    ap.add_argument("--layers", type=int, default=0, help="override the layer count (shape-preserving scale-down)")
+    ap.add_argument("--host-fraction", type=float, default=-1.0, help="share of chunks whose fp32 states live in pinned host memory")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--fused-check", action="store_true", help="take the overflow test inside the gradient pack instead of a separate pass")
+    ap.add_argument("--tune", default="", help="comma list key=value: bpc, unroll, nt, cbpc, threads, wg, cunroll")
+    return ap.parse_args()
+
+
+class State:
+    pass
+
+
+def setup(w, dev, host_fraction=0.0, staging_tile_elems=4 << 20, staging_slots=3):
+    """Allocate chunk lists and seeded inputs on the device (and pinned host memory for
+    host-resident chunks); pack the fp32 params; m = v = 0."""
+    import torch
+    from paper_2108_05818_amd import psx
+    from paper_2108_05818_amd import workloads as W
+
+    st = State()
+    st.w = w
+    st.C = w.chunk_elems
+    st.slots, st.used = psx.psx_chunk_layout(w.numel, st.C)
+    st.nch = len(st.used)
+    n_host = int(round(host_fraction * st.nch))
+    st.n_host = n_host
+    st.ctx = psx.psx_ctx_create(max_chunks=st.nch, max_tensors=len(w.numel),
+                                staging_tile_elems=staging_tile_elems if n_host else 0, staging_slots=staging_slots)
+    C = st.C
+    st.p16 = [torch.zeros(C, dtype=torch.float16, device=dev) for _ in range(st.nch)]
+    st.g16 = [torch.zeros(C, dtype=torch.float16, device=dev) for _ in range(st.nch)]
+    # seeded tensors (the "model"): fp32 params and one set of scaled fp16 gradients
+    st.p_t = [W.params_torch(s, w.seed + i, dev) for i, s in enumerate(w.numel)]
+    st.g_t = [W.grads_f16_torch(s, w.seed + 100000 + i, w.loss_scale, dev) for i, s in enumerate(w.numel)]
+    st.out_t = [torch.empty(s, dtype=torch.float16, device=dev) for s in w.numel]
+    # fp32 states: the first chunks in HBM, the last n_host chunks in pinned host memory
+    st.p32, st.m, st.v, st.host = [], [], [], []
+    first_host = st.nch - n_host
+    for k in range(st.nch):
+        if k < first_host:
+            st.p32.append(torch.zeros(C, dtype=torch.float32, device=dev))
+            st.m.append(torch.zeros(C, dtype=torch.float32, device=dev))
+            st.v.append(torch.zeros(C, dtype=torch.float32, device=dev))
+            st.host.append(None)
+        else:
+            st.p32.append(None); st.m.append(None); st.v.append(None)
+            st.host.append([torch.zeros(C, dtype=torch.float32).pin_memory() for _ in range(3)])
+    # pack the fp32 params: HBM chunks directly, host chunks through a device bounce chunk
+    if n_host == 0:
+        psx.psx_pack(st.ctx, psx.PSX_F32, st.p_t, st.slots, st.p32, C)
+    else:
+        tmp = [torch.zeros(C, dtype=torch.float32, device=dev) if st.p32[k] is None else st.p32[k] for k in range(st.nch)]
+        psx.psx_pack(st.ctx, psx.PSX_F32, st.p_t, st.slots, tmp, C)
+        torch.cuda.synchronize()
+        for k in range(first_host, st.nch):
+            st.host[k][0].copy_(tmp[k])
+        del tmp
+    torch.cuda.synchronize()
+    specs = []
+    for k in range(st.nch):
+        s = dict(g16=st.g16[k], p16=st.p16[k], used=st.used[k])
+        if st.host[k] is None:
+            s.update(p32=st.p32[k], m=st.m[k], v=st.v[k], loc_in=psx.PSX_LOC_HBM, loc_out=psx.PSX_LOC_HBM)
+        else:
+            s.update(p32_host=st.host[k][0], m_host=st.host[k][1], v_host=st.host[k][2],
+                     loc_in=psx.PSX_LOC_HOST, loc_out=psx.PSX_LOC_HOST)
+        specs.append(s)
+    st.chunks = psx.make_chunks(specs)
+    st.t_ptrs = psx.ptr_array(st.g_t)
+    st.o_ptrs = psx.ptr_array(st.out_t)
+    st.g16_ptrs = psx.ptr_array(st.g16)
+    st.p16_ptrs = psx.ptr_array(st.p16)
+    st.scaler = psx.make_scaler(w.loss_scale, w.growth_interval)
+    st.numel_arr = list(w.numel)
+    return st
+
+
+def run_step(st, fused_check=False):
+    """One pass of the hot path; returns the overflow flag."""
+    from paper_2108_05818_amd import psx
+    w, ctx, C = st.w, st.ctx, st.C
+    slots, used = psx.psx_chunk_layout(st.numel_arr, C)                       # a1
+    n = len(st.numel_arr)
+    if fused_check:
+        psx.psx_overflow_reset(ctx)
+        psx.psx_pack(ctx, psx.PSX_F16, st.t_ptrs, slots, st.g16, C, flags=psx.PSX_PACK_CHECK_OVERFLOW, n=n)   # a2 + a3
+        step_flags = psx.PSX_STEP_USE_FLAG
+    else:
+        psx.psx_pack(ctx, psx.PSX_F16, st.t_ptrs, slots, st.g16, C, n=n)     # a2
+        step_flags = psx.PSX_STEP_CHECK_FIRST                                 # a3 inside the step call
+    hp = psx.make_hyper(lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps, weight_decay=w.weight_decay,
+                        adamw_mode=w.adamw_mode, step=st.scaler.step, loss_scale=st.scaler.scale)
+    psx.psx_chunk_adam_step(ctx, st.chunks, hp, step_flags, n_chunks=st.nch)  # a4 / a5 / a6
+    psx.psx_unpack(ctx, psx.PSX_F16, st.o_ptrs, slots, st.p16, C, n=n)       # a2 (fp16 params back to tensors)
+    flag, _ = psx.psx_overflow_read(ctx)                                      # synchronises the stream
+    psx.psx_loss_scale_update(st.scaler, flag)                                # a7
+    return flag
+
+
+def cpu_baseline(st, target_chunks=8):
+    """The oracle, as it stands, on the host cores: one whole step (gradient pack, overflow check,
+    Adam, fp16 unpack) over the first tensors of the workload that fill `target_chunks` chunks.
+    Tensors and chunks are spread over threads; the oracle's own code is single-threaded C."""
+    import numpy as np
+    import oracle as orc
+
+    w, C = st.w, st.C
+    # prefix of the tensor list that ends on or before the end of chunk target_chunks-1
+    o_slots, o_used = orc.chunk_layout(w.numel, C)
+    T = 0
+    for i in range(len(w.numel)):
+        end = o_slots[i].chunk * C + o_slots[i].offset + o_slots[i].numel
+        if end > target_chunks * C:
+            break
+        T = i + 1
+    if T == 0:
+        T = 1
+    numel = w.numel[:T]
+    slots, used = orc.chunk_layout(numel, C)
+    nch = len(used)
+    n_elems = int(sum(numel))
+    threads = max(1, min(16, len(os.sched_getaffinity(0)), max(nch, 1)))
+    g_np = [st.g_t[i].view(__import__("torch").int16).cpu().numpy().view(np.uint16) for i in range(T)]
+    p_np = [st.p_t[i].cpu().numpy() for i in range(T)]
+    ch = dict(p32=[np.zeros(C, np.float32) for _ in range(nch)], m=[np.zeros(C, np.float32) for _ in range(nch)],
+              v=[np.zeros(C, np.float32) for _ in range(nch)], p16=[np.zeros(C, np.uint16) for _ in range(nch)],
+              g16=[np.zeros(C, np.uint16) for _ in range(nch)])
+    out = [np.zeros(s, np.uint16) for s in numel]
+    sub = lambda i: (orc.Slot * 1)(slots[i])
+    pool = ThreadPoolExecutor(threads)
+    list(pool.map(lambda i: orc.pack([p_np[i]], sub(i), ch["p32"], C), range(T)))          # untimed set-up
+    h = orc.hyper(lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps, weight_decay=w.weight_decay,
+                  adamw_mode=w.adamw_mode, step=1, loss_scale=w.loss_scale)
+    t0 = time.perf_counter()
+    orc.chunk_layout(numel, C)
+    list(pool.map(lambda i: orc.pack([g_np[i]], sub(i), ch["g16"], C), range(T)))
+    flags = list(pool.map(lambda k: orc.overflow_check([ch["g16"][k]], [used[k]])[0], range(nch)))
+    if not any(flags):
+        list(pool.map(lambda k: orc.adam_chunk(ch["g16"][k], ch["p16"][k], ch["p32"][k], ch["m"][k], ch["v"][k],
+                                               int(used[k]), h), range(nch)))
+    list(pool.map(lambda i: orc.unpack([out[i]], sub(i), ch["p16"], C), range(T)))
+    dt = time.perf_counter() - t0
+    pool.shutdown()
+    return {"value": n_elems / dt / 1e9, "unit": "Gelem/s", "cores": threads, "kind": "oracle",
+            "sample": f"one whole step on the first {T} tensors ({n_elems} elements, {nch} chunks of {C}) "
+                      f"of the same workload, {dt:.2f} s wall on {threads} threads"}
+
+
+def read_traffic(path):
+    """HBM bytes per Adam launch from the committed counter summary (None if absent)."""
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("traffic_bytes_per_launch:"):
+                    return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py measures one GPU: this path has no collectives and is not sharded here; "
+              "run with --gpus 1 (total throughput of N GPUs is N independent copies of this number).",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2108_05818_amd import psx
+    from paper_2108_05818_amd import workloads as W
+
+    if not os.path.exists(psx.LIB_PATH):
+        import __graft_entry__
+        __graft_entry__.build()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = "cuda:0"
+    if a.workload == "tiny":
+        w = W.config1_tiny()
+    elif a.workload == "gpt12b":
+        w = W.config4_gpt12b(a.layers or 40)
+    else:
+        w = W.config2_gpt1b(a.layers or 20)
+    host_fraction = w.host_fraction if a.host_fraction < 0 else a.host_fraction
+    st = setup(w, dev, host_fraction)
+    tune_keys = {"bpc": psx.PSX_TUNE_ADAM_BLOCKS_PER_CU, "unroll": psx.PSX_TUNE_ADAM_UNROLL,
+                 "nt": psx.PSX_TUNE_NONTEMPORAL, "cbpc": psx.PSX_TUNE_COPY_BLOCKS_PER_CU,
+                 "threads": psx.PSX_TUNE_ADAM_THREADS, "wg": psx.PSX_TUNE_ADAM_WG_PER_CU,
+                 "cunroll": psx.PSX_TUNE_COPY_UNROLL}
+    for kv in filter(None, a.tune.split(",")):
+        k, v = kv.split("=")
+        psx.psx_ctx_set_tuning(st.ctx, tune_keys[k], int(v))
+
+    cpu = None
+    if not a.no_cpu_baseline:
+        cpu = cpu_baseline(st)
+
+    psx.psx_ctx_set_profiling(st.ctx, 1)
+    for _ in range(a.warmup):
+        run_step(st, a.fused_check)
+    torch.cuda.synchronize()
+    phase = {"pack_ms": 0.0, "check_ms": 0.0, "adam_ms": 0.0, "spill_ms": 0.0}
+    t0 = time.perf_counter()
+    skipped = 0
+    for _ in range(a.steps):
+        skipped += run_step(st, a.fused_check)
+        tm = psx.psx_ctx_get_timing(st.ctx)      # events of this step; the stream is already drained
+        phase["pack_ms"] += tm.pack_ms; phase["check_ms"] += tm.check_ms
+        phase["adam_ms"] += tm.adam_ms; phase["spill_ms"] += tm.spill_ms
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms = dt * 1e3 / a.steps
+    n_elems = w.n_elems
+    for k in phase:
+        phase[k] /= a.steps
+    adam_elems = int(tm.adam_elems)
+    adam_bytes = ADAM_BYTES_PER_ELEM * adam_elems
+    achieved = adam_bytes / (phase["adam_ms"] * 1e-3) / 1e9 if phase["adam_ms"] > 0 else 0.0
+    traffic = read_traffic(os.path.join(ROOT, "profiles", "adam_kernel_gpt1b_hbm_traffic.txt")) \
+        if (a.workload == "gpt1b" and not a.layers and host_fraction == 0) else None
+    out = {
+        "metric": "chunked Adam Gelem/s (whole hot path per step: layout + grad pack + overflow check + fused Adam + fp16 unpack + loss-scale update)",
+        "value": n_elems / (ms * 1e-3) / 1e9,
+        "unit": "Gelem/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "n_elems": n_elems, "n_tensors": len(w.numel), "chunk_elems": w.chunk_elems,
+                   "n_chunks": st.nch, "host_resident_chunks": st.n_host, "loss_scale": w.loss_scale,
+                   "weight_decay": w.weight_decay, "fused_check": bool(a.fused_check), "skipped_steps": skipped},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "kernel": "psx::adam_kernel (resident chunks, one launch)",
+                     "bytes_per_launch": adam_bytes, "avg_launch_ms": phase["adam_ms"]},
+        "adam_only_gelem_s": adam_elems / (phase["adam_ms"] * 1e-3) / 1e9 if phase["adam_ms"] > 0 else None,
+        "phase_ms": phase,
+        "cpu_baseline": cpu,
+    }
+    if st.n_host:
+        link_s = phase["spill_ms"] * 1e-3
+        out["host_link"] = {"h2d_GBs": tm.h2d_bytes / link_s / 1e9 if link_s else None,
+                            "d2h_GBs": tm.d2h_bytes / link_s / 1e9 if link_s else None,
+                            "spill_elems": int(tm.spill_elems), "spill_ms": phase["spill_ms"]}
+    print(json.dumps(out))
+    psx.psx_ctx_destroy(st.ctx)
+
+
+if __name__ == "__main__":
+    main()

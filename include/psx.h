@@ -239,15 +239,22 @@ int32_t psx_loss_scale_update(psx_scaler *s, uint32_t overflow);
 
 /* ------------------------------------------------------------------ tuning and timing
  * Launch shape knobs (for sweeps; defaults are tuned for MI355X):
- *   PSX_TUNE_ADAM_BLOCKS_PER_CU  resident workgroups per CU of the Adam kernel (0 = one tile per workgroup)
+ *   PSX_TUNE_ADAM_BLOCKS_PER_CU  0 = one tile per workgroup, dispatched in order; n > 0 = n persistent
+ *                                workgroups per CU that stride over the tiles
  *   PSX_TUNE_ADAM_UNROLL         rows of 4 elements per thread per tile: 1, 2 or 4
  *   PSX_TUNE_NONTEMPORAL         0/1: non-temporal hints on the streaming loads and stores
  *   PSX_TUNE_COPY_BLOCKS_PER_CU  same as the first, for pack/unpack/check
+ *   PSX_TUNE_ADAM_THREADS        threads per workgroup of the Adam kernel: 64 or 256
+ *   PSX_TUNE_ADAM_WG_PER_CU      cap on Adam workgroups resident per CU (0 = none)
+ *   PSX_TUNE_COPY_UNROLL         16-byte vectors per thread and tile of pack/unpack: 1 or 4
  */
 #define PSX_TUNE_ADAM_BLOCKS_PER_CU 1u
 #define PSX_TUNE_ADAM_UNROLL        2u
 #define PSX_TUNE_NONTEMPORAL        3u
 #define PSX_TUNE_COPY_BLOCKS_PER_CU 4u
+#define PSX_TUNE_ADAM_THREADS       5u
+#define PSX_TUNE_ADAM_WG_PER_CU     6u
+#define PSX_TUNE_COPY_UNROLL        7u
 int32_t psx_ctx_set_tuning(psx_ctx *ctx, uint32_t key, int64_t value);
 
 /* Kernel timing with HIP events on the caller's stream (off by default). */

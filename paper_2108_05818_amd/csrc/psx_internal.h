@@ -47,17 +47,21 @@ struct AdamScalars {
 };
 
 struct Tuning {
-    int adam_blocks_per_cu = 8;
-    int adam_unroll = 2;
+    int adam_threads = 64;         // 64 or 256 threads per workgroup
+    int adam_unroll = 1;           // rows of 4 elements per thread
+    int adam_blocks_per_cu = 0;    // 0: one tile per workgroup; >0: persistent grid-stride
+    int adam_wg_per_cu = 14;       // cap on resident workgroups per CU (0: none)
     int nontemporal = 1;
-    int copy_blocks_per_cu = 8;
+    int copy_blocks_per_cu = 0;
+    int copy_unroll = 1;           // 16-byte vectors per thread and tile of pack/unpack: 1 or 4
 };
 
-// Elements per tile of the Adam kernel for a given unroll (256 threads x 4 elements x unroll).
+// Elements per tile of the Adam kernel (threads x 4 elements x unroll).
 constexpr uint32_t kThreads = 256;
-inline uint64_t adam_tile_elems(int unroll) { return (uint64_t)kThreads * 4u * (uint64_t)unroll; }
+inline uint64_t adam_tile_elems(const Tuning &t) { return (uint64_t)t.adam_threads * 4u * (uint64_t)t.adam_unroll; }
+constexpr uint64_t kRecastTileElems = (uint64_t)kThreads * 4u * 2u;
 constexpr uint64_t kCheckTileElems = (uint64_t)kThreads * 8u * 4u;   // 8192 fp16 per tile
-constexpr uint64_t kCopyTileBytes = (uint64_t)kThreads * 16u * 4u;   // 16 KiB per tile
+inline uint64_t copy_tile_bytes(const Tuning &t) { return (uint64_t)kThreads * 16u * (uint64_t)(t.copy_unroll == 1 ? 1 : 4); }
 
 // ---- launchers (psx_kernels.hip).  All enqueue on `s` and return the launch status. ----
 hipError_t launch_adam(const AdamRun *runs_dev, uint32_t n_runs, uint64_t n_tiles,

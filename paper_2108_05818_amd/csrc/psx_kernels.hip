@@ -85,13 +85,18 @@ __device__ __forceinline__ void adam_elem(float g, float &p, float &m, float &v,
     p = p - u;
 }
 
-template <int U, bool NT, int DM>
-__global__ __launch_bounds__(kThreads) void adam_kernel(const AdamRun *__restrict__ runs,
-                                                        uint32_t n_runs, uint64_t n_tiles,
-                                                        AdamScalars sc,
-                                                        const uint32_t *__restrict__ flag) {
+// T threads per workgroup, U rows of 4 elements per thread: a tile is T*4*U
+// elements of every stream.  Small tiles dispatched in order (one tile per
+// workgroup) keep the window of addresses the chip works on compact, which is
+// what the HBM controllers reward; the launch may also reserve LDS it never
+// touches, only to cap the workgroups resident per CU (see launch_adam).
+template <int T, int U, bool NT, int DM>
+__global__ __launch_bounds__(T) void adam_kernel(const AdamRun *__restrict__ runs,
+                                                 uint32_t n_runs, uint64_t n_tiles,
+                                                 AdamScalars sc,
+                                                 const uint32_t *__restrict__ flag) {
     if (flag != nullptr && *flag != 0) return;          // overflow: the whole step is skipped
-    constexpr uint32_t ROW = kThreads * 4;
+    constexpr uint32_t ROW = T * 4;
     constexpr uint32_t TILE = ROW * U;
     const uint32_t tid = threadIdx.x;
     for (uint64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
@@ -166,18 +171,38 @@ __global__ __launch_bounds__(kThreads) void adam_kernel(const AdamRun *__restric
     }
 }
 
-template <int U, bool NT>
+template <int T, int U, bool NT>
 static hipError_t launch_adam_dm(const AdamRun *runs, uint32_t n_runs, uint64_t n_tiles,
                                  const AdamScalars &sc, const uint32_t *flag, uint32_t grid,
-                                 hipStream_t s) {
+                                 uint32_t lds, hipStream_t s) {
     switch (sc.decay_mode) {
-        case 0: hipLaunchKernelGGL((adam_kernel<U, NT, 0>), dim3(grid), dim3(kThreads), 0, s, runs, n_runs, n_tiles, sc, flag); break;
-        case 1: hipLaunchKernelGGL((adam_kernel<U, NT, 1>), dim3(grid), dim3(kThreads), 0, s, runs, n_runs, n_tiles, sc, flag); break;
-        default: hipLaunchKernelGGL((adam_kernel<U, NT, 2>), dim3(grid), dim3(kThreads), 0, s, runs, n_runs, n_tiles, sc, flag); break;
+        case 0: hipLaunchKernelGGL((adam_kernel<T, U, NT, 0>), dim3(grid), dim3(T), lds, s, runs, n_runs, n_tiles, sc, flag); break;
+        case 1: hipLaunchKernelGGL((adam_kernel<T, U, NT, 1>), dim3(grid), dim3(T), lds, s, runs, n_runs, n_tiles, sc, flag); break;
+        default: hipLaunchKernelGGL((adam_kernel<T, U, NT, 2>), dim3(grid), dim3(T), lds, s, runs, n_runs, n_tiles, sc, flag); break;
     }
     return hipGetLastError();
 }
 
+template <int T, bool NT>
+static hipError_t launch_adam_u(int unroll, const AdamRun *runs, uint32_t n_runs, uint64_t n_tiles,
+                                const AdamScalars &sc, const uint32_t *flag, uint32_t grid,
+                                uint32_t lds, hipStream_t s) {
+    switch (unroll) {
+        case 1: return launch_adam_dm<T, 1, NT>(runs, n_runs, n_tiles, sc, flag, grid, lds, s);
+        case 4: return launch_adam_dm<T, 4, NT>(runs, n_runs, n_tiles, sc, flag, grid, lds, s);
+        default: return launch_adam_dm<T, 2, NT>(runs, n_runs, n_tiles, sc, flag, grid, lds, s);
+    }
+}
+
+// Bytes of LDS to reserve per workgroup so that at most wg_per_cu workgroups
+// fit the 160 KiB of a CU (0 = no cap).  The kernels never touch it.
+static uint32_t throttle_lds(int wg_per_cu) {
+    if (wg_per_cu <= 0) return 0;
+    if (wg_per_cu < 3) wg_per_cu = 3;                    // stay under the 64 KiB dynamic-LDS default
+    return (uint32_t)((160u * 1024u / (uint32_t)wg_per_cu) & ~511u);
+}
+
+// blocks_per_cu == 0: one tile per workgroup, handed out in order by the dispatcher.
 static uint32_t grid_for(uint64_t n_tiles, int blocks_per_cu, int n_cu) {
     uint64_t cap = blocks_per_cu > 0 ? (uint64_t)blocks_per_cu * (uint64_t)n_cu : 0x7FFFFFFFull;
     if (cap > 0x7FFFFFFFull) cap = 0x7FFFFFFFull;
@@ -189,15 +214,13 @@ hipError_t launch_adam(const AdamRun *runs, uint32_t n_runs, uint64_t n_tiles, c
                        const uint32_t *flag, const Tuning &t, int n_cu, hipStream_t s) {
     if (n_tiles == 0) return hipSuccess;
     const uint32_t grid = grid_for(n_tiles, t.adam_blocks_per_cu, n_cu);
+    const uint32_t lds = throttle_lds(t.adam_wg_per_cu);
     const bool nt = t.nontemporal != 0;
-    switch (t.adam_unroll) {
-        case 1: return nt ? launch_adam_dm<1, true>(runs, n_runs, n_tiles, sc, flag, grid, s)
-                          : launch_adam_dm<1, false>(runs, n_runs, n_tiles, sc, flag, grid, s);
-        case 4: return nt ? launch_adam_dm<4, true>(runs, n_runs, n_tiles, sc, flag, grid, s)
-                          : launch_adam_dm<4, false>(runs, n_runs, n_tiles, sc, flag, grid, s);
-        default: return nt ? launch_adam_dm<2, true>(runs, n_runs, n_tiles, sc, flag, grid, s)
-                           : launch_adam_dm<2, false>(runs, n_runs, n_tiles, sc, flag, grid, s);
-    }
+    if (t.adam_threads == 64)
+        return nt ? launch_adam_u<64, true>(t.adam_unroll, runs, n_runs, n_tiles, sc, flag, grid, lds, s)
+                  : launch_adam_u<64, false>(t.adam_unroll, runs, n_runs, n_tiles, sc, flag, grid, lds, s);
+    return nt ? launch_adam_u<256, true>(t.adam_unroll, runs, n_runs, n_tiles, sc, flag, grid, lds, s)
+              : launch_adam_u<256, false>(t.adam_unroll, runs, n_runs, n_tiles, sc, flag, grid, lds, s);
 }
 
 // ------------------------------------------------------------------ re-cast on a skipped step
@@ -311,7 +334,7 @@ hipError_t launch_check(const AdamRun *runs, uint32_t n_runs, uint64_t n_tiles, 
 
 // ------------------------------------------------------------------ pack / unpack
 // One segment = one contiguous piece of a tensor inside one chunk.  A tile is
-// 16 KiB of it.  The destination is brought to 16-byte alignment with a few
+// U x 4 KiB of it.  The destination is brought to 16-byte alignment with a few
 // single-element copies, then written with 16-byte stores; the source is read
 // with 16-byte loads when it happens to share that alignment, else with
 // 4-byte or 2-byte loads (every access is naturally aligned).
@@ -330,12 +353,12 @@ __device__ __forceinline__ uint32_t test_vec(const u32x4 &w) {
         return 0;
 }
 
-template <int ES, bool CHECK, bool NT>
+template <int ES, bool CHECK, bool NT, int U>
 __global__ __launch_bounds__(kThreads) void copy_kernel(const CopySeg *__restrict__ segs,
                                                         uint32_t n_segs, uint64_t n_tiles,
                                                         uint32_t *flag, uint32_t *per_chunk) {
     typedef typename ElemT<ES>::type E;
-    constexpr uint32_t TILE_BYTES = (uint32_t)kCopyTileBytes;
+    constexpr uint32_t TILE_BYTES = kThreads * 16u * U;
     constexpr uint32_t TILE_ELEMS = TILE_BYTES / ES;
     const uint32_t tid = threadIdx.x;
     for (uint64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
@@ -351,13 +374,13 @@ __global__ __launch_bounds__(kThreads) void copy_kernel(const CopySeg *__restric
         if (head > nbytes) head = nbytes;
         const uint32_t mis = (uint32_t)(reinterpret_cast<uintptr_t>(s + head) & 15u);
         if (head == 0 && mis == 0 && nbytes == TILE_BYTES) {
-            // whole aligned tile: four 16-byte loads in flight per lane, then four stores
-            u32x4 w[4];
+            // whole aligned tile: U 16-byte loads in flight per lane, then U stores
+            u32x4 w[U];
 #pragma unroll
-            for (int u = 0; u < 4; u++)
+            for (int u = 0; u < U; u++)
                 w[u] = ld<NT>(gptr<u32x4>(s) + u * kThreads + tid);
 #pragma unroll
-            for (int u = 0; u < 4; u++) {
+            for (int u = 0; u < U; u++) {
                 bad |= test_vec<ES, CHECK>(w[u]);
                 st<NT>(gptr<u32x4>(d) + u * kThreads + tid, w[u]);
             }
@@ -415,8 +438,15 @@ hipError_t launch_copy(const CopySeg *segs, uint32_t n_segs, uint64_t n_tiles, u
     const uint32_t grid = grid_for(n_tiles, t.copy_blocks_per_cu, n_cu);
     const bool check = flag != nullptr;
     const bool nt = t.nontemporal != 0;
-#define PSX_LAUNCH_COPY(ES, CH, NT_) \
-    hipLaunchKernelGGL((copy_kernel<ES, CH, NT_>), dim3(grid), dim3(kThreads), 0, s, segs, n_segs, n_tiles, flag, per_chunk)
+#define PSX_LAUNCH_COPY(ES, CH, NT_)                                                                          \
+    do {                                                                                                      \
+        if (t.copy_unroll == 1)                                                                               \
+            hipLaunchKernelGGL((copy_kernel<ES, CH, NT_, 1>), dim3(grid), dim3(kThreads), 0, s, segs, n_segs, \
+                               n_tiles, flag, per_chunk);                                                     \
+        else                                                                                                  \
+            hipLaunchKernelGGL((copy_kernel<ES, CH, NT_, 4>), dim3(grid), dim3(kThreads), 0, s, segs, n_segs, \
+                               n_tiles, flag, per_chunk);                                                     \
+    } while (0)
     if (elem_size == 2) {
         if (check) { if (nt) PSX_LAUNCH_COPY(2, true, true); else PSX_LAUNCH_COPY(2, true, false); }
         else       { if (nt) PSX_LAUNCH_COPY(2, false, true); else PSX_LAUNCH_COPY(2, false, false); }

@@ -239,6 +239,18 @@ extern "C" int32_t psx_ctx_set_tuning(psx_ctx *c, uint32_t key, int64_t value) {
             if (value < 0 || value > 64) return fail(PSX_EINVAL, "copy blocks per CU must be 0..64");
             c->tune.copy_blocks_per_cu = (int)value;
             break;
+        case PSX_TUNE_COPY_UNROLL:
+            if (value != 1 && value != 4) return fail(PSX_EINVAL, "copy unroll must be 1 or 4");
+            c->tune.copy_unroll = (int)value;
+            break;
+        case PSX_TUNE_ADAM_THREADS:
+            if (value != 64 && value != 256) return fail(PSX_EINVAL, "adam threads must be 64 or 256");
+            c->tune.adam_threads = (int)value;
+            break;
+        case PSX_TUNE_ADAM_WG_PER_CU:
+            if (value < 0 || value > 64) return fail(PSX_EINVAL, "adam workgroups per CU must be 0..64");
+            c->tune.adam_wg_per_cu = (int)value;
+            break;
         default:
             return fail(PSX_EINVAL, "psx_ctx_set_tuning: unknown key %u", key);
     }
@@ -300,7 +312,7 @@ int32_t build_segments(psx_ctx *c, const char *who, uint32_t dtype, const void *
     if (n_chunks > c->cfg.max_chunks) return fail(PSX_ECAP, "%s: %zu chunks, context holds %llu", who, n_chunks, (unsigned long long)c->cfg.max_chunks);
     if (n > c->cfg.max_tensors) return fail(PSX_ECAP, "%s: %zu tensors, context holds %llu", who, n, (unsigned long long)c->cfg.max_tensors);
     const uint32_t es = dtype == PSX_F16 ? 2u : 4u;
-    const uint64_t tile_elems = kCopyTileBytes / es;
+    const uint64_t tile_elems = copy_tile_bytes(c->tune) / es;
     const uint64_t total = (uint64_t)n_chunks * chunk_elems;
     for (size_t k = 0; k < n_chunks; k++) {
         if (chunks[k] == nullptr) return fail(PSX_EINVAL, "%s: chunk %zu is NULL", who, k);
@@ -509,8 +521,8 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
     hipStream_t s = static_cast<hipStream_t>(stream);
 
     // ---- build the descriptor table: [resident | recast | check | spill tiles]
-    const uint64_t adam_tile = adam_tile_elems(c->tune.adam_unroll);
-    const uint64_t recast_tile = adam_tile_elems(2);
+    const uint64_t adam_tile = adam_tile_elems(c->tune);
+    const uint64_t recast_tile = kRecastTileElems;
     c->runs.clear();
     uint64_t res_tiles = 0, res_elems = 0;
     for (size_t k = 0; k < n_chunks; k++) {

@@ -204,10 +204,14 @@ RAGGED_USED = [1, 3, 4, 5, 1023, 1024, 1025, 2047, 2049, 4096, 4097, 8191, 12289
 
 
 @pytest.mark.parametrize("wd,adamw", [(0.0, 0), (0.01, 0), (0.01, 1)])
-@pytest.mark.parametrize("unroll,nt", [(1, 1), (2, 0), (2, 1), (4, 1)])
-def test_adam_matches_oracle_over_ragged_chunks(orc, ctx, wd, adamw, unroll, nt):
-    psx.psx_ctx_set_tuning(ctx, psx.PSX_TUNE_ADAM_UNROLL, unroll)
-    psx.psx_ctx_set_tuning(ctx, psx.PSX_TUNE_NONTEMPORAL, nt)
+@pytest.mark.parametrize("threads,unroll,nt,bpc", [(64, 1, 1, 0), (64, 2, 0, 0), (64, 4, 1, 2), (256, 1, 1, 0),
+                                                    (256, 2, 1, 4), (256, 4, 0, 0)])
+def test_adam_matches_oracle_over_ragged_chunks(orc, ctx, wd, adamw, threads, unroll, nt, bpc):
+    """Every launch shape the tuning knobs can select computes the same bits."""
+    defaults = [(psx.PSX_TUNE_ADAM_THREADS, 64), (psx.PSX_TUNE_ADAM_UNROLL, 1), (psx.PSX_TUNE_NONTEMPORAL, 1),
+                (psx.PSX_TUNE_ADAM_BLOCKS_PER_CU, 0)]
+    for key, val in zip([d[0] for d in defaults], (threads, unroll, nt, bpc)):
+        psx.psx_ctx_set_tuning(ctx, key, val)
     try:
         Cn = 20000
         cl = ChunkLists(RAGGED_USED, Cn)
@@ -224,8 +228,8 @@ def test_adam_matches_oracle_over_ragged_chunks(orc, ctx, wd, adamw, unroll, nt)
             check_recast_of_own_params(orc, cl)
         assert worst == 0.0, f"expected bit-exact, got {worst} ulp"
     finally:
-        psx.psx_ctx_set_tuning(ctx, psx.PSX_TUNE_ADAM_UNROLL, 2)
-        psx.psx_ctx_set_tuning(ctx, psx.PSX_TUNE_NONTEMPORAL, 1)
+        for key, val in defaults:
+            psx.psx_ctx_set_tuning(ctx, key, val)
 
 
 def test_adam_closed_forms_on_gpu(ctx):
