@@ -35,6 +35,9 @@ def parse():
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (shape-preserving scale-down)")
     ap.add_argument("--host-fraction", type=float, default=-1.0, help="share of chunks whose fp32 states live in pinned host memory")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
+                    help="also launch psx_copy_bytes once over this many MiB (a plain copy of known size, "
+                         "the yardstick the HBM traffic counters are scaled by)")
     ap.add_argument("--fused-check", action="store_true", help="take the overflow test inside the gradient pack instead of a separate pass")
     ap.add_argument("--tune", default="", help="comma list key=value: bpc, unroll, nt, cbpc, threads, wg, cunroll")
     return ap.parse_args()
@@ -225,6 +228,13 @@ def main():
         k, v = kv.split("=")
         psx.psx_ctx_set_tuning(st.ctx, tune_keys[k], int(v))
 
+    if a.copy_calibration:
+        nb = a.copy_calibration << 20
+        src = torch.ones(nb // 4, dtype=torch.float32, device=dev)
+        dst = torch.zeros_like(src)
+        psx.psx_copy_bytes(st.ctx, dst, src, nb)
+        torch.cuda.synchronize()
+        del src, dst
     cpu = None
     if not a.no_cpu_baseline:
         cpu = cpu_baseline(st)
