@@ -96,7 +96,7 @@ def _ptr(a):
 
 
 def _ptr_array(arrays):
-    return (C.c_void_p * len(arrays))(*[a.ctypes.data for a in arrays])
+    return (C.c_void_p * len(arrays))(*[None if a is None else a.ctypes.data for a in arrays])
 
 
 def _check(a, dtype):
@@ -141,17 +141,18 @@ def slots_as_tuples(slots, n):
 
 
 def pack(tensors, slots, chunks, chunk_elems):
-    """tensors: list of 1-D numpy arrays; chunks: list of 1-D numpy arrays (same dtype)."""
-    es = chunks[0].dtype.itemsize
+    """tensors: list of 1-D numpy arrays; chunks: list of 1-D numpy arrays (same dtype); a chunk may
+    be None (not materialised: its elements are skipped)."""
+    es = next(c for c in chunks if c is not None).dtype.itemsize
     for t in tensors:
         assert t.dtype.itemsize == es and t.flags.c_contiguous
     for c in chunks:
-        assert c.size == chunk_elems and c.flags.c_contiguous
+        assert c is None or (c.size == chunk_elems and c.flags.c_contiguous)
     lib().orc_pack(_ptr_array(tensors), slots, len(tensors), _ptr_array(chunks), chunk_elems, es)
 
 
 def unpack(tensors, slots, chunks, chunk_elems):
-    es = chunks[0].dtype.itemsize
+    es = next(c for c in chunks if c is not None).dtype.itemsize
     for t in tensors:
         assert t.dtype.itemsize == es and t.flags.c_contiguous
     lib().orc_unpack(_ptr_array(tensors), slots, len(tensors), _ptr_array(chunks), chunk_elems, es)

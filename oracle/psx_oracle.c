@@ -177,7 +177,9 @@ int orc_chunk_layout(const uint64_t *numel, uint64_t n, uint64_t chunk_elems,
 /* temporary memory into that piece).  Byte copies, elem_size bytes    */
 /* per element.  The chunk list is read as one virtual array of        */
 /* n_chunks*chunk_elems elements, so an oversized tensor simply runs   */
-/* on into the next chunk.  Fragments are never touched.               */
+/* on into the next chunk.  Fragments are never touched.  A NULL entry  */
+/* in chunks[] means "this chunk is not materialised here": elements   */
+/* that belong to it are skipped (lets a test hold a sample of chunks). */
 /* ------------------------------------------------------------------ */
 
 void orc_pack(const void *const *tensors, const orc_slot *slots, uint64_t n,
@@ -187,6 +189,7 @@ void orc_pack(const void *const *tensors, const orc_slot *slots, uint64_t n,
         const unsigned char *src = (const unsigned char *)tensors[i];
         uint64_t lin = (uint64_t)slots[i].chunk * chunk_elems + slots[i].offset;
         for (uint64_t k = 0; k < slots[i].numel; k++, lin++) {
+            if (chunks[lin / chunk_elems] == NULL) continue;
             unsigned char *dst = (unsigned char *)chunks[lin / chunk_elems]
                                  + (lin % chunk_elems) * elem_size;
             for (uint64_t b = 0; b < elem_size; b++) dst[b] = src[k * elem_size + b];
@@ -201,6 +204,7 @@ void orc_unpack(void *const *tensors, const orc_slot *slots, uint64_t n,
         unsigned char *dst = (unsigned char *)tensors[i];
         uint64_t lin = (uint64_t)slots[i].chunk * chunk_elems + slots[i].offset;
         for (uint64_t k = 0; k < slots[i].numel; k++, lin++) {
+            if (chunks[lin / chunk_elems] == NULL) continue;
             const unsigned char *src = (const unsigned char *)chunks[lin / chunk_elems]
                                        + (lin % chunk_elems) * elem_size;
             for (uint64_t b = 0; b < elem_size; b++) dst[k * elem_size + b] = src[b];

@@ -84,3 +84,27 @@ def test_overflow_max_finite_is_not_flagged(orc):
     chunks = [np.array([0x7BFF, 0xFBFF, 0x0001, 0x8001, 0x0000, 0x8000, 0x03FF], np.uint16)]
     flag, per = orc.overflow_check(chunks, np.array([7], np.uint64))
     assert flag == 0 and per[0] == 0
+
+
+def test_pack_into_a_sample_of_chunks_equals_full_pack(orc):
+    rng = np.random.default_rng(15)
+    numel = [int(x) for x in rng.integers(0, 200, size=40)] + [700, 3]
+    C = 128
+    slots, used = orc.chunk_layout(numel, C)
+    tensors = [rng.integers(0, 60000, size=s).astype(np.uint16) for s in numel]
+    full = _mk_chunks(len(used), C, np.uint16, 9)
+    orc.pack(tensors, slots, full, C)
+    keep = set(int(k) for k in rng.choice(len(used), size=len(used) // 2, replace=False))
+    part = [np.full(C, 9, np.uint16) if k in keep else None for k in range(len(used))]
+    orc.pack(tensors, slots, part, C)
+    for k in keep:
+        assert part[k].tobytes() == full[k].tobytes()
+    out_full = [np.zeros(s, np.uint16) for s in numel]
+    out_part = [np.zeros(s, np.uint16) for s in numel]
+    orc.unpack(out_full, slots, full, C)
+    orc.unpack(out_part, slots, part, C)
+    for i, s in enumerate(numel):      # elements living in kept chunks come back, the others stay zero
+        lin = slots[i].chunk * C + slots[i].offset + np.arange(s)
+        inside = np.isin(lin // C, list(keep))
+        assert np.array_equal(out_part[i][inside], out_full[i][inside])
+        assert not out_part[i][~inside].any()
