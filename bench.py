@@ -22,6 +22,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+CPU_BASELINE_TENSORS = 64      # the oracle leg reads a prefix of the tensor list, never more than this
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 ADAM_BYTES_PER_ELEM = 28       # read g16 2 + p,m,v 12; write p,m,v 12 + p16 2
 
@@ -39,6 +40,8 @@ def parse():
                     help="also launch psx_copy_bytes once over this many MiB (a plain copy of known size, "
                          "the yardstick the HBM traffic counters are scaled by)")
     ap.add_argument("--fused-check", action="store_true", help="take the overflow test inside the gradient pack instead of a separate pass")
+    ap.add_argument("--staging-tile", type=int, default=4 << 20, help="elements per staging tile (host-resident chunks)")
+    ap.add_argument("--staging-slots", type=int, default=3)
     ap.add_argument("--tune", default="", help="comma list key=value: bpc, unroll, nt, cbpc, threads, wg, cunroll")
     return ap.parse_args()
 
@@ -47,9 +50,10 @@ class State:
     pass
 
 
-def setup(w, dev, host_fraction=0.0, staging_tile_elems=4 << 20, staging_slots=3):
+def setup(w, dev, host_fraction=0.0, staging_tile_elems=4 << 20, staging_slots=3, keep_params="all"):
     """Allocate chunk lists and seeded inputs on the device (and pinned host memory for
-    host-resident chunks); pack the fp32 params; m = v = 0."""
+    host-resident chunks); pack the fp32 params tensor by tensor; m = v = 0.
+    keep_params: "all" keeps every fp32 source tensor, an int keeps only the first that many."""
     import torch
     from paper_2108_05818_amd import psx
     from paper_2108_05818_amd import workloads as W
@@ -66,10 +70,6 @@ def setup(w, dev, host_fraction=0.0, staging_tile_elems=4 << 20, staging_slots=3
     C = st.C
     st.p16 = [torch.zeros(C, dtype=torch.float16, device=dev) for _ in range(st.nch)]
     st.g16 = [torch.zeros(C, dtype=torch.float16, device=dev) for _ in range(st.nch)]
-    # seeded tensors (the "model"): fp32 params and one set of scaled fp16 gradients
-    st.p_t = [W.params_torch(s, w.seed + i, dev) for i, s in enumerate(w.numel)]
-    st.g_t = [W.grads_f16_torch(s, w.seed + 100000 + i, w.loss_scale, dev) for i, s in enumerate(w.numel)]
-    st.out_t = [torch.empty(s, dtype=torch.float16, device=dev) for s in w.numel]
     # fp32 states: the first chunks in HBM, the last n_host chunks in pinned host memory
     st.p32, st.m, st.v, st.host = [], [], [], []
     first_host = st.nch - n_host
@@ -81,18 +81,23 @@ def setup(w, dev, host_fraction=0.0, staging_tile_elems=4 << 20, staging_slots=3
             st.host.append(None)
         else:
             st.p32.append(None); st.m.append(None); st.v.append(None)
-            st.host.append([torch.zeros(C, dtype=torch.float32).pin_memory() for _ in range(3)])
-    # pack the fp32 params: HBM chunks directly, host chunks through a device bounce chunk
-    if n_host == 0:
-        psx.psx_pack(st.ctx, psx.PSX_F32, st.p_t, st.slots, st.p32, C)
-    else:
-        tmp = [torch.zeros(C, dtype=torch.float32, device=dev) if st.p32[k] is None else st.p32[k] for k in range(st.nch)]
-        psx.psx_pack(st.ctx, psx.PSX_F32, st.p_t, st.slots, tmp, C)
-        torch.cuda.synchronize()
-        for k in range(first_host, st.nch):
-            st.host[k][0].copy_(tmp[k])
-        del tmp
+            # a host-resident chunk needs room for its used prefix only (pinned memory is scarce)
+            st.host.append([psx.PinnedF32(st.used[k]) for _ in range(3)])
+    # seeded tensors (the "model"): fp32 params, packed one tensor at a time straight into the chunk
+    # that will hold them (pinned host chunks are device-accessible, so the pack kernel writes them too),
+    # and one set of scaled fp16 gradients
+    p32_dst = psx.ptr_array([st.p32[k] if st.host[k] is None else st.host[k][0] for k in range(st.nch)])
+    st.p_t = []
+    for i, s in enumerate(w.numel):
+        t = W.params_torch(s, w.seed + i, dev)
+        one = (psx.psx_slot * 1)(st.slots[i])
+        lib_chunks = p32_dst
+        psx.lib().psx_pack(st.ctx, psx.PSX_F32, psx.ptr_array([t]), one, 1, lib_chunks, st.nch, C, 0,
+                           torch.cuda.current_stream().cuda_stream)
+        st.p_t.append(t if keep_params == "all" or i < keep_params else None)
     torch.cuda.synchronize()
+    st.g_t = [W.grads_f16_torch(s, w.seed + 100000 + i, w.loss_scale, dev) for i, s in enumerate(w.numel)]
+    st.out_t = [torch.empty(s, dtype=torch.float16, device=dev) for s in w.numel]
     specs = []
     for k in range(st.nch):
         s = dict(g16=st.g16[k], p16=st.p16[k], used=st.used[k])
@@ -105,8 +110,6 @@ def setup(w, dev, host_fraction=0.0, staging_tile_elems=4 << 20, staging_slots=3
     st.chunks = psx.make_chunks(specs)
     st.t_ptrs = psx.ptr_array(st.g_t)
     st.o_ptrs = psx.ptr_array(st.out_t)
-    st.g16_ptrs = psx.ptr_array(st.g16)
-    st.p16_ptrs = psx.ptr_array(st.p16)
     st.scaler = psx.make_scaler(w.loss_scale, w.growth_interval)
     st.numel_arr = list(w.numel)
     return st
@@ -145,7 +148,7 @@ def cpu_baseline(st, target_chunks=8):
     # prefix of the tensor list that ends on or before the end of chunk target_chunks-1
     o_slots, o_used = orc.chunk_layout(w.numel, C)
     T = 0
-    for i in range(len(w.numel)):
+    for i in range(min(len(w.numel), CPU_BASELINE_TENSORS)):
         end = o_slots[i].chunk * C + o_slots[i].offset + o_slots[i].numel
         if end > target_chunks * C:
             break
@@ -219,11 +222,14 @@ def main():
     else:
         w = W.config2_gpt1b(a.layers or 20)
     host_fraction = w.host_fraction if a.host_fraction < 0 else a.host_fraction
-    st = setup(w, dev, host_fraction)
+    # the fp32 source tensors are needed again only by the oracle leg, and only the first few of them
+    st = setup(w, dev, host_fraction, a.staging_tile, a.staging_slots,
+               keep_params=0 if a.no_cpu_baseline else CPU_BASELINE_TENSORS)
     tune_keys = {"bpc": psx.PSX_TUNE_ADAM_BLOCKS_PER_CU, "unroll": psx.PSX_TUNE_ADAM_UNROLL,
                  "nt": psx.PSX_TUNE_NONTEMPORAL, "cbpc": psx.PSX_TUNE_COPY_BLOCKS_PER_CU,
                  "threads": psx.PSX_TUNE_ADAM_THREADS, "wg": psx.PSX_TUNE_ADAM_WG_PER_CU,
-                 "cunroll": psx.PSX_TUNE_COPY_UNROLL}
+                 "cunroll": psx.PSX_TUNE_COPY_UNROLL, "hostmode": psx.PSX_TUNE_HOST_MODE,
+                 "hostgrid": psx.PSX_TUNE_HOST_GRID, "hostunroll": psx.PSX_TUNE_HOST_UNROLL}
     for kv in filter(None, a.tune.split(",")):
         k, v = kv.split("=")
         psx.psx_ctx_set_tuning(st.ctx, tune_keys[k], int(v))
@@ -282,9 +288,19 @@ def main():
     }
     if st.n_host:
         link_s = phase["spill_ms"] * 1e-3
-        out["host_link"] = {"h2d_GBs": tm.h2d_bytes / link_s / 1e9 if link_s else None,
-                            "d2h_GBs": tm.d2h_bytes / link_s / 1e9 if link_s else None,
-                            "spill_elems": int(tm.spill_elems), "spill_ms": phase["spill_ms"]}
+        r = psx.psx_measure_link(st.ctx, 1024, 5)      # same copy streams as the pipeline, pinned memory
+        peak = {"copy_h2d_alone_GBs": r.h2d_alone, "copy_d2h_alone_GBs": r.d2h_alone,
+                "copy_each_way_both_at_once_GBs": r.each_way_both, "copy_MiB": 1024}
+        h2d = tm.h2d_bytes / link_s / 1e9 if link_s else None
+        # denominator: the best pinned-copy rate one direction reaches on this machine in this run (copies in
+        # both directions at once reach less than that with this runtime; both figures are listed)
+        out["host_link"] = {"bound": "host link, 12 B/element each way, both directions at once",
+                            "h2d_GBs": h2d, "d2h_GBs": tm.d2h_bytes / link_s / 1e9 if link_s else None,
+                            "measured_peak": peak,
+                            "frac": h2d / max(r.h2d_alone, r.d2h_alone) if h2d else None,
+                            "frac_of_copies_both_at_once": h2d / r.each_way_both if h2d else None,
+                            "spill_elems": int(tm.spill_elems), "spill_ms": phase["spill_ms"],
+                            "spill_gelem_s": tm.spill_elems / link_s / 1e9 if link_s else None}
     print(json.dumps(out))
     psx.psx_ctx_destroy(st.ctx)
 

@@ -189,8 +189,12 @@ typedef struct psx_adam_hyper {
  * buffers (Sec. "Device-aware Operator Placement": as many optimizer-state
  * chunks as fit stay in GPU memory, the rest in host memory):
  *   HBM  -> HBM  : updated in place in p32/m/v.
- *   HOST -> HOST : streamed tile by tile through the context's staging
- *                  (H2D, update, D2H); p32/m/v may be NULL.
+ *   HOST -> HOST : by default the kernel reads and writes the pinned buffers
+ *                  directly over the host link (one launch on a side stream,
+ *                  concurrent with the resident chunks; the buffers must be
+ *                  device-accessible, as hipHostMalloc memory is); with
+ *                  PSX_TUNE_HOST_MODE 0 they are streamed tile by tile through
+ *                  the context's staging (H2D, update, D2H).  p32/m/v may be NULL.
  *   HOST -> HBM  : copied into p32/m/v, updated there (chunk admitted).
  *   HBM  -> HOST : updated in p32/m/v, then copied to the host buffers (chunk
  *                  evicted; the device buffers keep a copy the caller may drop).
@@ -247,6 +251,12 @@ int32_t psx_loss_scale_update(psx_scaler *s, uint32_t overflow);
  *   PSX_TUNE_ADAM_THREADS        threads per workgroup of the Adam kernel: 64 or 256
  *   PSX_TUNE_ADAM_WG_PER_CU      cap on Adam workgroups resident per CU (0 = none)
  *   PSX_TUNE_COPY_UNROLL         16-byte vectors per thread and tile of pack/unpack: 1 or 4
+ *   PSX_TUNE_HOST_MODE           host-resident (HOST -> HOST) chunks: 0 = staged through device tiles with
+ *                                H2D / D2H copies on the copy streams; 1 = the kernel reads and writes the
+ *                                pinned buffers directly over the host link (they must be device-accessible,
+ *                                which hipHostMalloc memory is)
+ *   PSX_TUNE_HOST_GRID           mode 1: persistent workgroups of that launch
+ *   PSX_TUNE_HOST_UNROLL         mode 1: rows of 4 elements per thread: 1, 2 or 4
  */
 #define PSX_TUNE_ADAM_BLOCKS_PER_CU 1u
 #define PSX_TUNE_ADAM_UNROLL        2u
@@ -255,6 +265,9 @@ int32_t psx_loss_scale_update(psx_scaler *s, uint32_t overflow);
 #define PSX_TUNE_ADAM_THREADS       5u
 #define PSX_TUNE_ADAM_WG_PER_CU     6u
 #define PSX_TUNE_COPY_UNROLL        7u
+#define PSX_TUNE_HOST_MODE          8u
+#define PSX_TUNE_HOST_GRID          9u
+#define PSX_TUNE_HOST_UNROLL        10u
 int32_t psx_ctx_set_tuning(psx_ctx *ctx, uint32_t key, int64_t value);
 
 /* Kernel timing with HIP events on the caller's stream (off by default). */
@@ -274,6 +287,21 @@ int32_t psx_ctx_get_timing(psx_ctx *ctx, psx_timing *out);
 /* Plain device copy of n_bytes (a multiple of 16, 16-byte aligned pointers), the
  * reference kernel the bandwidth counters and the Adam kernel are scaled against. */
 int32_t psx_copy_bytes(psx_ctx *ctx, void *dst, const void *src, uint64_t n_bytes, void *stream);
+
+/* Page-locked, device-accessible host memory for host-resident chunks (hipHostMalloc with default
+ * flags).  A host-resident chunk needs room for its `used` elements only.  Synchronous. */
+int32_t psx_pinned_alloc(uint64_t n_bytes, void **out);
+int32_t psx_pinned_free(void *ptr);
+
+/* Pinned-memory copy rates of this machine's host link, measured with hipMemcpyAsync on the
+ * context's own two copy streams (the ones host-resident chunks are streamed on): each direction
+ * alone, then both directions at once.  GB/s (1e9 bytes) per direction; best of `reps` passes after
+ * two warm-up passes.  Allocates and frees two pinned and two device buffers of `mib` MiB.
+ * Synchronous.  A measurement aid: the denominator for the host-resident part of the step. */
+typedef struct psx_link_rates {
+    double h2d_alone, d2h_alone, each_way_both;
+} psx_link_rates;
+int32_t psx_measure_link(psx_ctx *ctx, uint64_t mib, uint32_t reps, psx_link_rates *out);
 
 #ifdef __cplusplus
 }

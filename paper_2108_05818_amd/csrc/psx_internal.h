@@ -54,6 +54,10 @@ struct Tuning {
     int nontemporal = 1;
     int copy_blocks_per_cu = 0;
     int copy_unroll = 1;           // 16-byte vectors per thread and tile of pack/unpack: 1 or 4
+    int host_mode = 1;             // host-resident chunks: 0 staged H2D/kernel/D2H, 1 kernel works on pinned memory
+    int host_grid = 32;            // direct mode: persistent workgroups (256 threads) of the host launch
+    int host_unroll = 1;           // direct mode: rows of 4 elements per thread
+    int grid_override = 0;         // internal: absolute grid size of a launch (0: derive from blocks_per_cu)
 };
 
 // Elements per tile of the Adam kernel (threads x 4 elements x unroll).

@@ -213,7 +213,8 @@ static uint32_t grid_for(uint64_t n_tiles, int blocks_per_cu, int n_cu) {
 hipError_t launch_adam(const AdamRun *runs, uint32_t n_runs, uint64_t n_tiles, const AdamScalars &sc,
                        const uint32_t *flag, const Tuning &t, int n_cu, hipStream_t s) {
     if (n_tiles == 0) return hipSuccess;
-    const uint32_t grid = grid_for(n_tiles, t.adam_blocks_per_cu, n_cu);
+    const uint32_t grid = t.grid_override > 0 ? (uint32_t)(n_tiles < (uint64_t)t.grid_override ? n_tiles : (uint64_t)t.grid_override)
+                                              : grid_for(n_tiles, t.adam_blocks_per_cu, n_cu);
     const uint32_t lds = throttle_lds(t.adam_wg_per_cu);
     const bool nt = t.nontemporal != 0;
     if (t.adam_threads == 64)
@@ -258,7 +259,8 @@ __global__ __launch_bounds__(kThreads) void recast_kernel(const AdamRun *__restr
 hipError_t launch_recast_if_flag(const AdamRun *runs, uint32_t n_runs, uint64_t n_tiles,
                                  const uint32_t *flag, const Tuning &t, int n_cu, hipStream_t s) {
     if (n_tiles == 0) return hipSuccess;
-    const uint32_t grid = grid_for(n_tiles, t.adam_blocks_per_cu, n_cu);
+    const uint32_t grid = t.grid_override > 0 ? (uint32_t)(n_tiles < (uint64_t)t.grid_override ? n_tiles : (uint64_t)t.grid_override)
+                                              : grid_for(n_tiles, t.adam_blocks_per_cu, n_cu);
     hipLaunchKernelGGL(recast_kernel, dim3(grid), dim3(kThreads), 0, s, runs, n_runs, n_tiles, flag);
     return hipGetLastError();
 }

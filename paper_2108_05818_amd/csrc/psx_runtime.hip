@@ -1,6 +1,7 @@
 // Host runtime behind the C ABI: context, descriptor tables, the multi-tensor
 // pack/unpack and overflow-check calls, and the Adam step with its
 // double-buffered H2D / update / D2H pipeline for host-resident chunks.
+#include <chrono>
 #include <cmath>
 #include <cstring>
 #include <vector>
@@ -243,6 +244,18 @@ extern "C" int32_t psx_ctx_set_tuning(psx_ctx *c, uint32_t key, int64_t value) {
             if (value != 1 && value != 4) return fail(PSX_EINVAL, "copy unroll must be 1 or 4");
             c->tune.copy_unroll = (int)value;
             break;
+        case PSX_TUNE_HOST_MODE:
+            if (value != 0 && value != 1) return fail(PSX_EINVAL, "host mode must be 0 (staged copies) or 1 (direct access)");
+            c->tune.host_mode = (int)value;
+            break;
+        case PSX_TUNE_HOST_GRID:
+            if (value < 1 || value > 65536) return fail(PSX_EINVAL, "host grid must be 1..65536 workgroups");
+            c->tune.host_grid = (int)value;
+            break;
+        case PSX_TUNE_HOST_UNROLL:
+            if (value != 1 && value != 2 && value != 4) return fail(PSX_EINVAL, "host unroll must be 1, 2 or 4");
+            c->tune.host_unroll = (int)value;
+            break;
         case PSX_TUNE_ADAM_THREADS:
             if (value != 64 && value != 256) return fail(PSX_EINVAL, "adam threads must be 64 or 256");
             c->tune.adam_threads = (int)value;
@@ -292,6 +305,63 @@ extern "C" int32_t psx_copy_bytes(psx_ctx *c, void *dst, const void *src, uint64
     int32_t rc = set_device_guard(c);
     if (rc != PSX_OK) return rc;
     PSX_HIP(launch_copy_bytes(dst, src, n_bytes, c->tune, c->n_cu, static_cast<hipStream_t>(stream)));
+    return PSX_OK;
+}
+
+extern "C" int32_t psx_pinned_alloc(uint64_t n_bytes, void **out) {
+    if (out == nullptr) return fail(PSX_EINVAL, "psx_pinned_alloc: out is NULL");
+    *out = nullptr;
+    if (n_bytes == 0) return fail(PSX_EINVAL, "psx_pinned_alloc: zero bytes");
+    PSX_HIP(hipHostMalloc(out, n_bytes, hipHostMallocDefault));
+    return PSX_OK;
+}
+
+extern "C" int32_t psx_pinned_free(void *ptr) {
+    if (ptr == nullptr) return PSX_OK;
+    PSX_HIP(hipHostFree(ptr));
+    return PSX_OK;
+}
+
+extern "C" int32_t psx_measure_link(psx_ctx *c, uint64_t mib, uint32_t reps, psx_link_rates *out) {
+    if (c == nullptr || out == nullptr) return fail(PSX_EINVAL, "psx_measure_link: NULL argument");
+    if (mib == 0 || mib > 16384 || reps == 0) return fail(PSX_EINVAL, "psx_measure_link: mib must be 1..16384, reps > 0");
+    int32_t rc = set_device_guard(c);
+    if (rc != PSX_OK) return rc;
+    const size_t nb = (size_t)mib << 20;
+    void *h_src = nullptr, *h_dst = nullptr, *d_in = nullptr, *d_out = nullptr;
+    auto cleanup = [&]() {
+        if (h_src) (void)hipHostFree(h_src);
+        if (h_dst) (void)hipHostFree(h_dst);
+        if (d_in) (void)hipFree(d_in);
+        if (d_out) (void)hipFree(d_out);
+    };
+#define PSX_TRY(call) do { hipError_t e_ = (call); if (e_ != hipSuccess) { cleanup(); return fail(PSX_EHIP, "%s -> %s", #call, hipGetErrorString(e_)); } } while (0)
+    PSX_TRY(hipHostMalloc(&h_src, nb, hipHostMallocDefault));
+    PSX_TRY(hipHostMalloc(&h_dst, nb, hipHostMallocDefault));
+    PSX_TRY(hipMalloc(&d_in, nb));
+    PSX_TRY(hipMalloc(&d_out, nb));
+    memset(h_src, 1, nb);
+    memset(h_dst, 0, nb);
+    PSX_TRY(hipMemset(d_out, 2, nb));
+    PSX_TRY(hipDeviceSynchronize());
+    double best[3] = {0, 0, 0};
+    for (int mode = 0; mode < 3; mode++) {                  // 0 H2D alone, 1 D2H alone, 2 both
+        for (uint32_t r = 0; r < reps + 2; r++) {
+            const auto t0 = std::chrono::steady_clock::now();
+            if (mode != 1) PSX_TRY(hipMemcpyAsync(d_in, h_src, nb, hipMemcpyHostToDevice, c->h2d));
+            if (mode != 0) PSX_TRY(hipMemcpyAsync(h_dst, d_out, nb, hipMemcpyDeviceToHost, c->d2h));
+            PSX_TRY(hipStreamSynchronize(c->h2d));
+            PSX_TRY(hipStreamSynchronize(c->d2h));
+            const double dt = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
+            const double rate = (double)nb / dt / 1e9;
+            if (r >= 2 && rate > best[mode]) best[mode] = rate;
+        }
+    }
+#undef PSX_TRY
+    cleanup();
+    out->h2d_alone = best[0];
+    out->d2h_alone = best[1];
+    out->each_way_both = best[2];
     return PSX_OK;
 }
 
@@ -514,7 +584,8 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
         if (host_side) {
             if (!ch.p32_host || !ch.m_host || !ch.v_host) return fail(PSX_EINVAL, "psx_chunk_adam_step: chunk %zu needs pinned p32/m/v", k);
             if (!aligned16(ch.p32_host) || !aligned16(ch.m_host) || !aligned16(ch.v_host)) return fail(PSX_EALIGN, "psx_chunk_adam_step: chunk %zu host states not 16-byte aligned", k);
-            if (T == 0) return fail(PSX_ENOSTAGING, "psx_chunk_adam_step: chunk %zu is host-resident but the context has no staging", k);
+            const bool staged = !(c->tune.host_mode == 1 && ch.loc_in == PSX_LOC_HOST && ch.loc_out == PSX_LOC_HOST);
+            if (staged && T == 0) return fail(PSX_ENOSTAGING, "psx_chunk_adam_step: chunk %zu is host-resident but the context has no staging", k);
         }
     }
     if ((rc = set_device_guard(c)) != PSX_OK) return rc;
@@ -551,11 +622,17 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
     std::vector<SpillTile> tiles;
     uint64_t spill_elems = 0, h2d_bytes = 0, d2h_bytes = 0;
     uint64_t slot_counter = 0;
+    const bool direct = c->tune.host_mode == 1;
     for (size_t k = 0; k < n_chunks; k++) {
         const psx_chunk &ch = chunks[k];
         if (ch.used == 0 || (ch.loc_in == PSX_LOC_HBM && ch.loc_out == PSX_LOC_HBM)) continue;
         const bool in_host = ch.loc_in == PSX_LOC_HOST, out_host = ch.loc_out == PSX_LOC_HOST;
         spill_elems += ch.used;
+        if (direct && in_host && out_host) {          // handled below: the kernel works on the host buffers
+            h2d_bytes += 3 * ch.used * sizeof(float);
+            d2h_bytes += 3 * ch.used * sizeof(float);
+            continue;
+        }
         for (uint64_t off = 0; off < ch.used; off += T) {
             const uint64_t n = ch.used - off < T ? ch.used - off : T;
             SpillTile t{};
@@ -585,19 +662,33 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
             tiles.push_back(t);
         }
     }
+    // host-resident chunks updated in place over the link: the kernel reads and writes pinned memory
+    Tuning td = c->tune;
+    td.adam_threads = 256; td.adam_unroll = c->tune.host_unroll; td.adam_wg_per_cu = 0;
+    td.grid_override = c->tune.host_grid;
+    const uint64_t direct_tile = adam_tile_elems(td);
+    const size_t direct_off = c->runs.size();
+    uint64_t direct_tiles = 0, direct_recast_tiles = 0;
+    size_t n_direct = 0, n_direct_recast = 0;
+    if (direct) {
+        for (size_t k = 0; k < n_chunks; k++) {
+            const psx_chunk &ch = chunks[k];
+            if (ch.used == 0 || ch.loc_in != PSX_LOC_HOST || ch.loc_out != PSX_LOC_HOST) continue;
+            direct_tiles += push_run(c->runs, ch.g16, ch.p16, ch.p32_host, ch.m_host, ch.v_host, ch.used, direct_tiles, direct_tile, (uint32_t)k);
+        }
+        n_direct = c->runs.size() - direct_off;
+        if (use_flag)
+            for (size_t k = 0; k < n_chunks; k++) {
+                const psx_chunk &ch = chunks[k];
+                if (ch.used == 0 || ch.loc_in != PSX_LOC_HOST || ch.loc_out != PSX_LOC_HOST || ch.g16 != ch.p16) continue;
+                direct_recast_tiles += push_run(c->runs, ch.g16, ch.p16, ch.p32_host, ch.m_host, ch.v_host, ch.used, direct_recast_tiles, recast_tile, (uint32_t)k);
+            }
+        n_direct_recast = c->runs.size() - direct_off - n_direct;
+    }
     if (c->runs.size() > 0xFFFFFFFFull) return fail(PSX_ECAP, "psx_chunk_adam_step: too many runs");
     if ((rc = table_upload(c->adam_tbl, c->runs.data(), c->runs.size() * sizeof(AdamRun), s)) != PSX_OK) return rc;
     const AdamRun *tbl = static_cast<const AdamRun *>(c->adam_tbl.dev);
     const uint32_t *flag = use_flag ? c->flags_dev : nullptr;
-
-    // ---- copy streams may start once earlier work on the caller's stream is done
-    if (!tiles.empty()) {
-        PSX_HIP(hipEventRecord(c->ev_entry, s));
-        PSX_HIP(hipStreamWaitEvent(c->h2d, c->ev_entry, 0));
-        PSX_HIP(hipStreamWaitEvent(c->d2h, c->ev_entry, 0));
-        c->t_spill.valid = false;
-        if (c->prof) PSX_HIP(hipEventRecord(c->t_spill.a, c->h2d));
-    }
 
     // ---- overflow check over every gradient chunk
     if (check_first) {
@@ -605,6 +696,16 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
         if ((rc = span_begin(c, c->t_check, s)) != PSX_OK) return rc;
         PSX_HIP(launch_check(tbl + n_res + n_recast, (uint32_t)n_check, check_tiles, c->flags_dev, c->flags_dev + 1, c->tune, c->n_cu, s));
         if ((rc = span_end(c, c->t_check, s)) != PSX_OK) return rc;
+    }
+
+    // ---- the side streams may start once earlier work on the caller's stream (and the check) is done
+    const bool any_side = !tiles.empty() || n_direct != 0;
+    c->t_spill.valid = false;
+    if (any_side) {
+        PSX_HIP(hipEventRecord(c->ev_entry, s));
+        PSX_HIP(hipStreamWaitEvent(c->h2d, c->ev_entry, 0));
+        PSX_HIP(hipStreamWaitEvent(c->d2h, c->ev_entry, 0));
+        if (c->prof) PSX_HIP(hipEventRecord(c->t_spill.a, c->h2d));
     }
 
     // ---- HBM-resident chunks: one launch over all of them
@@ -618,10 +719,19 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
             PSX_HIP(launch_recast_if_flag(tbl + n_res, (uint32_t)n_recast, recast_tiles, flag, c->tune, c->n_cu, s));
     }
 
-    // ---- chunks with a host side: H2D (copy stream) -> update (caller's stream) -> D2H (copy stream)
+    // ---- host-resident chunks, direct mode: one persistent launch on the side stream, concurrent with
+    // the resident launch; every load and store of p/m/v crosses the host link once, in both directions at once
     c->spill_elems = spill_elems; c->h2d_bytes = h2d_bytes; c->d2h_bytes = d2h_bytes;
-    const size_t ring = c->ev_k.size();
     bool any_h2d = false, any_d2h = false;
+    if (n_direct != 0) {
+        PSX_HIP(launch_adam(tbl + direct_off, (uint32_t)n_direct, direct_tiles, sc, flag, td, c->n_cu, c->h2d));
+        if (n_direct_recast != 0)
+            PSX_HIP(launch_recast_if_flag(tbl + direct_off + n_direct, (uint32_t)n_direct_recast, direct_recast_tiles, flag, td, c->n_cu, c->h2d));
+        any_h2d = true;
+    }
+
+    // ---- chunks with a host side, staged: H2D (copy stream) -> update (caller's stream) -> D2H (copy stream)
+    const size_t ring = c->ev_k.size();
     for (size_t i = 0; i < tiles.size(); i++) {
         const SpillTile &t = tiles[i];
         const size_t e = i % ring;
@@ -649,7 +759,7 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
             PSX_HIP(hipEventRecord(c->ev_free[e], s));
         }
     }
-    if (!tiles.empty()) {
+    if (any_side) {
         if (any_h2d) { PSX_HIP(hipEventRecord(c->ev_h2d_end, c->h2d)); PSX_HIP(hipStreamWaitEvent(s, c->ev_h2d_end, 0)); }
         if (any_d2h) { PSX_HIP(hipEventRecord(c->ev_d2h_end, c->d2h)); PSX_HIP(hipStreamWaitEvent(s, c->ev_d2h_end, 0)); }
         if (c->prof) { PSX_HIP(hipEventRecord(c->t_spill.b, s)); c->t_spill.valid = true; }

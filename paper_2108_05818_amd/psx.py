@@ -20,12 +20,13 @@ PSX_LOC_HBM, PSX_LOC_HOST = 0, 1
 PSX_STEP_USE_FLAG, PSX_STEP_CHECK_FIRST = 1, 2
 PSX_TUNE_ADAM_BLOCKS_PER_CU, PSX_TUNE_ADAM_UNROLL, PSX_TUNE_NONTEMPORAL, PSX_TUNE_COPY_BLOCKS_PER_CU = 1, 2, 3, 4
 PSX_TUNE_ADAM_THREADS, PSX_TUNE_ADAM_WG_PER_CU, PSX_TUNE_COPY_UNROLL = 5, 6, 7
+PSX_TUNE_HOST_MODE, PSX_TUNE_HOST_GRID, PSX_TUNE_HOST_UNROLL = 8, 9, 10
 
 EXPORTS = [
     "psx_last_error", "psx_chunk_layout", "psx_ctx_create", "psx_ctx_destroy", "psx_pack", "psx_unpack",
     "psx_overflow_check", "psx_overflow_reset", "psx_overflow_read", "psx_chunk_adam_step",
     "psx_loss_scale_update", "psx_ctx_set_tuning", "psx_ctx_set_profiling", "psx_ctx_get_timing",
-    "psx_copy_bytes",
+    "psx_copy_bytes", "psx_measure_link", "psx_pinned_alloc", "psx_pinned_free",
 ]
 
 
@@ -67,6 +68,10 @@ class psx_timing(C.Structure):
                 ("d2h_bytes", C.c_uint64)]
 
 
+class psx_link_rates(C.Structure):
+    _fields_ = [("h2d_alone", C.c_double), ("d2h_alone", C.c_double), ("each_way_both", C.c_double)]
+
+
 _lib = None
 
 
@@ -98,6 +103,9 @@ def lib():
         "psx_ctx_set_profiling": [vp, C.c_int32],
         "psx_ctx_get_timing": [vp, C.POINTER(psx_timing)],
         "psx_copy_bytes": [vp, vp, vp, u64, vp],
+        "psx_measure_link": [vp, u64, u32, C.POINTER(psx_link_rates)],
+        "psx_pinned_alloc": [u64, C.POINTER(vp)],
+        "psx_pinned_free": [vp],
     }
     for name, args in sigs.items():
         f = getattr(L, name)
@@ -246,3 +254,41 @@ def psx_ctx_get_timing(ctx):
 
 def psx_copy_bytes(ctx, dst, src, n_bytes, stream=None):
     _ok(lib().psx_copy_bytes(ctx, _addr(dst), _addr(src), n_bytes, _stream(stream)))
+
+
+def psx_measure_link(ctx, mib=1024, reps=5):
+    r = psx_link_rates()
+    _ok(lib().psx_measure_link(ctx, mib, reps, C.byref(r)))
+    return r
+
+
+def psx_pinned_alloc(n_bytes):
+    """-> integer address of page-locked, device-accessible host memory."""
+    out = C.c_void_p(0)
+    _ok(lib().psx_pinned_alloc(n_bytes, C.byref(out)))
+    return out.value
+
+
+def psx_pinned_free(addr):
+    _ok(lib().psx_pinned_free(C.c_void_p(addr)))
+
+
+class PinnedF32:
+    """n float32 elements of pinned host memory from psx_pinned_alloc, with a numpy view.
+    `data_ptr()` makes it usable wherever the binding takes a tensor."""
+
+    def __init__(self, n, fill=0.0):
+        import numpy as np
+        self.n = int(n)
+        self.addr = psx_pinned_alloc(max(self.n, 1) * 4)
+        self.np = np.ctypeslib.as_array((C.c_float * max(self.n, 1)).from_address(self.addr))[:self.n]
+        self.np[...] = fill
+
+    def data_ptr(self):
+        return self.addr
+
+    def free(self):
+        if self.addr:
+            self.np = None
+            psx_pinned_free(self.addr)
+            self.addr = 0

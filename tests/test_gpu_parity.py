@@ -318,10 +318,13 @@ def test_overflow_skips_the_whole_step(orc, ctx, alias):
 
 # ---------------------------------------------------------------------------------- host-resident chunks
 
-@pytest.mark.parametrize("slots", [2, 3])
+@pytest.mark.parametrize("slots,mode", [(2, 0), (3, 0), (3, 1)])
 @pytest.mark.parametrize("alias", [False, True])
-def test_host_resident_chunks_stream_through_staging(orc, alias, slots):
+def test_host_resident_chunks_stream_through_staging(orc, alias, slots, mode):
+    """mode 0: staged H2D / kernel / D2H; mode 1: the kernel works on the pinned buffers over the link."""
     ctx = psx.psx_ctx_create(max_chunks=64, max_tensors=16, staging_tile_elems=4096, staging_slots=slots)
+    psx.psx_ctx_set_tuning(ctx, psx.PSX_TUNE_HOST_MODE, mode)
+    psx.psx_ctx_set_tuning(ctx, psx.PSX_TUNE_HOST_GRID, 7)
     try:
         used = [20000, 4096, 12289, 1, 4097, 0, 16384, 9000]
         loc = [(G, G), (H, H), (H, H), (H, H), (H, G), (H, H), (G, H), (H, H)]
@@ -363,9 +366,14 @@ def test_bad_arguments_touch_nothing():
         cl = ChunkLists([64], 64)
         fill_state(cl, 1, 1.0)
         hs = [torch.zeros(64).pin_memory() for _ in range(3)]
-        spec = cl.specs(loc=[(H, H)], host=[hs])
+        # staged host-resident chunks, and chunks changing residence, need a context with staging
+        psx.psx_ctx_set_tuning(ctx, psx.PSX_TUNE_HOST_MODE, 0)
         with pytest.raises(psx.PsxError) as e:
-            psx.psx_chunk_adam_step(ctx, psx.make_chunks(spec), psx.make_hyper())
+            psx.psx_chunk_adam_step(ctx, psx.make_chunks(cl.specs(loc=[(H, H)], host=[hs])), psx.make_hyper())
+        assert e.value.code == psx.PSX_ENOSTAGING
+        psx.psx_ctx_set_tuning(ctx, psx.PSX_TUNE_HOST_MODE, 1)
+        with pytest.raises(psx.PsxError) as e:
+            psx.psx_chunk_adam_step(ctx, psx.make_chunks(cl.specs(loc=[(H, G)], host=[hs])), psx.make_hyper())
         assert e.value.code == psx.PSX_ENOSTAGING
         with pytest.raises(psx.PsxError) as e:      # misaligned chunk base
             bad = cl.specs()
