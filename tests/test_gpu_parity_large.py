@@ -222,3 +222,123 @@ def test_config3_scaled_down_200_steps_with_random_injection(orc):
         assert doubled >= 1                                          # halvings and doublings both happened
     finally:
         psx.psx_ctx_destroy(ctx)
+
+
+# ---------------------------------------------------------------------------------- host-resident chunks at real shapes
+
+H, G = psx.PSX_LOC_HOST, psx.PSX_LOC_HBM
+
+
+def compare_sample_states(sm, st, where, tag):
+    """Sampled chunks against the oracle mirror, reading each chunk's states where they live now:
+    `where[k]` is None (device) or the three pinned buffers (used prefix only)."""
+    for k in sm.ks:
+        u = st.used[k]
+        for j, (name, mine) in enumerate((("p32", sm.p32[k]), ("m", sm.m[k]), ("v", sm.v[k]))):
+            if where[k] is None:
+                got = f32((st.p32[k], st.m[k], st.v[k])[j])
+                assert got[u:].tobytes() == mine[u:].tobytes(), f"{tag}: chunk {k} {name} padding"
+            else:
+                got = where[k][j].np
+            assert got[:u].tobytes() == mine[:u].tobytes(), f"{tag}: chunk {k} {name}"
+        assert bits16(st.p16[k]).tobytes() == sm.p16[k].tobytes(), f"{tag}: chunk {k} p16"
+
+
+@pytest.mark.parametrize("mode", [1, 0])
+def test_config4_shape_host_resident_chunks(orc, mode):
+    """GPT-12.6B tensor shapes (hidden 5120, 64 Mi chunks) at 4 layers; the last 40 % of the chunks keep
+    their fp32 states in pinned host memory.  mode 1: kernel works over the link; mode 0: staged copies."""
+    w = W.config4_gpt12b(layers=4)
+    st = bench.setup(w, DEV, host_fraction=0.4)
+    try:
+        psx.psx_ctx_set_tuning(st.ctx, psx.PSX_TUNE_HOST_MODE, mode)
+        first_host = st.nch - st.n_host
+        assert st.n_host == round(0.4 * st.nch) and st.host[first_host] is not None and st.host[first_host - 1] is None
+        sm = Sample(orc, st, [0, first_host - 1, first_host, st.nch - 1])
+        sm.pack(st.p_t, sm.p32)
+        where = [None if st.host[k] is None else st.host[k] for k in range(st.nch)]
+        compare_sample_states(sm, st, where, "after param pack")
+        for step in range(2):
+            flag = bench.run_step(st)
+            torch.cuda.synchronize()
+            sm.pack(st.g_t, sm.g16, as_bits16=True)
+            assert flag == sm.flag() == 0
+            sm.adam(orc.hyper(lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps, weight_decay=w.weight_decay,
+                              adamw_mode=w.adamw_mode, step=step + 1, loss_scale=w.loss_scale))
+            compare_sample_states(sm, st, where, f"mode {mode} step {step}")
+        tm = psx.psx_ctx_get_timing(st.ctx)
+        host_elems = sum(st.used[first_host:])
+        assert tm.spill_elems == host_elems and tm.h2d_bytes == tm.d2h_bytes == 12 * host_elems
+    finally:
+        psx.psx_ctx_destroy(st.ctx)
+        for hs in st.host:
+            for b in hs or []:
+                b.free()
+
+
+def test_config5_shape_residency_changes_every_step(orc):
+    """GPT-20B tensor shapes (hidden 6144, 64 Mi chunks) at 2 layers.  The share of chunks whose fp32 states
+    may stay in HBM moves by +-30 % per step (seeded), so chunks at the boundary of the resident prefix are
+    admitted (HOST -> HBM) or evicted (HBM -> HOST) while they are updated; most chunks stay on the host."""
+    w = W.config5_gpt20b(layers=2)
+    st = bench.setup(w, DEV, host_fraction=0.0)          # device homes for every chunk; host homes added here
+    ctx = psx.psx_ctx_create(max_chunks=st.nch, max_tensors=len(w.numel), staging_tile_elems=4 << 20, staging_slots=3)
+    host = [[psx.PinnedF32(st.used[k]) for _ in range(3)] for k in range(st.nch)]
+    try:
+        nch = st.nch
+        prefix = lambda t: max(1, min(nch - 1, round(nch * W.budget_fraction(t, 0.3, w.budget_jitter, w.seed))))
+        r = prefix(0)
+        sizes = [prefix(t) for t in range(1, 7)]
+        assert len(set(sizes)) > 2 and max(sizes) < 0.5 * nch          # the boundary really moves; most chunks on host
+        # initial residence: chunks >= r live on the host (their device homes are filled with garbage)
+        for k in range(r, nch):
+            for j, d in enumerate((st.p32[k], st.m[k], st.v[k])):
+                host[k][j].np[...] = d[:st.used[k]].cpu().numpy()
+                d.view(torch.int32).fill_(0x0BADBEEF)
+        loc = [G if k < r else H for k in range(nch)]
+        sm = Sample(orc, st, sorted({0, min(sizes) - 1, min(sizes), max(sizes) - 1, max(sizes), nch - 1}))
+        sm.pack(st.p_t, sm.p32)
+        slots, used = psx.psx_chunk_layout(w.numel, st.C)
+        moved = 0
+        for step in range(1, 7):
+            r_new = prefix(step)
+            new_loc = [G if k < r_new else H for k in range(nch)]
+            moved += sum(a != b for a, b in zip(loc, new_loc))
+            specs = [dict(g16=st.g16[k], p16=st.p16[k], p32=st.p32[k], m=st.m[k], v=st.v[k], used=st.used[k],
+                          p32_host=host[k][0], m_host=host[k][1], v_host=host[k][2],
+                          loc_in=loc[k], loc_out=new_loc[k]) for k in range(nch)]
+            psx.psx_pack(ctx, psx.PSX_F16, st.g_t, slots, st.g16, st.C)
+            hp = dict(lr=w.lr, weight_decay=w.weight_decay, step=step, loss_scale=w.loss_scale)
+            psx.psx_chunk_adam_step(ctx, psx.make_chunks(specs), psx.make_hyper(**hp), psx.PSX_STEP_CHECK_FIRST)
+            flag, _ = psx.psx_overflow_read(ctx)
+            torch.cuda.synchronize()
+            # link bytes are exactly what the residency of this step implies, nothing is moved twice
+            tm = psx.psx_ctx_get_timing(ctx)
+            assert tm.h2d_bytes == 12 * sum(st.used[k] for k in range(nch) if loc[k] == H)
+            assert tm.d2h_bytes == 12 * sum(st.used[k] for k in range(nch) if new_loc[k] == H)
+            # evicted chunks: poison the device home so that a stale read would show
+            for k in range(nch):
+                if loc[k] == G and new_loc[k] == H:
+                    for d in (st.p32[k], st.m[k], st.v[k]):
+                        d.view(torch.int32).fill_(0x0BADBEEF)
+            loc = new_loc
+            if step == 1:
+                sm.pack(st.g_t, sm.g16, as_bits16=True)
+            assert flag == sm.flag() == 0
+            sm.adam(orc.hyper(**hp))
+            where = [None if loc[k] == G else host[k] for k in range(nch)]
+            # device homes of sampled resident chunks were zero-initialised by the set-up, like the mirror
+            for k in sm.ks:
+                u = st.used[k]
+                bufs = (st.p32[k], st.m[k], st.v[k]) if where[k] is None else None
+                for j, mine in enumerate((sm.p32[k], sm.m[k], sm.v[k])):
+                    got = f32(bufs[j])[:u] if bufs else where[k][j].np
+                    assert got.tobytes() == mine[:u].tobytes(), f"step {step}: chunk {k} state {j}"
+                assert bits16(st.p16[k]).tobytes() == sm.p16[k].tobytes(), f"step {step}: chunk {k} p16"
+        assert moved >= 3
+    finally:
+        psx.psx_ctx_destroy(ctx)
+        psx.psx_ctx_destroy(st.ctx)
+        for hs in host:
+            for b in hs:
+                b.free()
