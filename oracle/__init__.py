@@ -13,6 +13,8 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "psx_oracle.c")
 _LIB = os.path.join(_HERE, "libpsx_oracle.so")
+# the mutation test points this at deliberately broken builds to prove that the pins notice them
+_LIB_OVERRIDE = os.environ.get("PSX_ORACLE_LIB")
 
 CFLAGS = ["-O2", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared", "-std=c11", "-Wall"]
 
@@ -53,8 +55,11 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        build(force=False)
-        L = C.CDLL(_LIB)
+        if _LIB_OVERRIDE:
+            L = C.CDLL(_LIB_OVERRIDE)
+        else:
+            build(force=False)
+            L = C.CDLL(_LIB)
         L.orc_f16_to_f32.restype = C.c_float
         L.orc_f16_to_f32.argtypes = [C.c_uint16]
         L.orc_f32_to_f16.restype = C.c_uint16
