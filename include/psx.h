@@ -288,6 +288,31 @@ int32_t psx_ctx_get_timing(psx_ctx *ctx, psx_timing *out);
  * reference kernel the bandwidth counters and the Adam kernel are scaled against. */
 int32_t psx_copy_bytes(psx_ctx *ctx, void *dst, const void *src, uint64_t n_bytes, void *stream);
 
+/* ------------------------------------------------------------------ placement and chunk size
+ * Device-aware placement of optimizer-state chunks (Sec. "Device-aware Operator Placement": as many
+ * optimizer-state chunks as fit the GPU margin space stay in GPU memory) specialised to the ADAM stage,
+ * which scans every chunk once per step.  A resident chunk takes 12*chunk_elems bytes of the budget; a
+ * host-resident chunk crosses the link with 12*used[k] bytes in each direction at every step.  The plan
+ * keeps the floor(budget / (12*chunk_elems)) fullest chunks in HBM (ties: lower index first), which
+ * minimises the link bytes of every step; for a growing budget the resident sets are nested, so a moving
+ * budget only moves chunks at the margin.  (On this cyclic scan the farthest-next-use rule of Sec. "Chunk
+ * Eviction Strategy" always evicts the chunk just updated, so in steady state a fixed set stays resident
+ * and the rest streams; which set is a free choice, taken here to minimise link bytes.)
+ * used[n_chunks]  host, in;  loc[n_chunks] host, out: PSX_LOC_HBM / PSX_LOC_HOST;
+ * host_elems      host, out, may be NULL: sum of used[] over host-resident chunks.  Pure host code. */
+int32_t psx_plan_residency(const uint64_t *used, size_t n_chunks, uint64_t chunk_elems,
+                           uint64_t hbm_budget_bytes, uint8_t *loc, uint64_t *host_elems);
+
+/* Chunk-size search (Sec. "Evaluation Methodology", "Chunk Size Searching"): try chunk sizes lo, lo+step,
+ * ... <= hi (elements), lay the tensor list out with each (psx_chunk_layout with `flags`), and return the
+ * size with the highest utilisation sum(numel) / (n_chunks*chunk_elems); ties go to the smaller size.
+ * Sizes for which PSX_LAYOUT_STRICT refuses a tensor, or whose four chunk lists (14 bytes per element of
+ * chunk capacity) exceed max_model_data_bytes (0 = no limit), are skipped; PSX_ETOOLARGE if none is left.
+ * best_util and best_n_chunks may be NULL.  Pure host code; allocates nothing. */
+int32_t psx_chunk_size_search(const uint64_t *numel, size_t n, uint64_t lo, uint64_t hi, uint64_t step,
+                              uint32_t flags, uint64_t max_model_data_bytes, uint64_t *best_chunk_elems,
+                              double *best_util, size_t *best_n_chunks);
+
 /* Page-locked, device-accessible host memory for host-resident chunks (hipHostMalloc with default
  * flags).  A host-resident chunk needs room for its `used` elements only.  Synchronous. */
 int32_t psx_pinned_alloc(uint64_t n_bytes, void **out);

@@ -88,6 +88,8 @@ def lib():
         L.orc_recast_chunk.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64]
         L.orc_chunk_adam_step.restype = C.c_uint32
         L.orc_chunk_adam_step.argtypes = [C.c_void_p] * 6 + [C.c_uint64, C.POINTER(AdamHyper)]
+        L.orc_min_link_bytes.restype = C.c_uint64
+        L.orc_min_link_bytes.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint64, C.c_void_p]
         L.orc_scaler_update.restype = None
         L.orc_scaler_update.argtypes = [C.POINTER(Scaler), C.c_uint32]
         _lib = L
@@ -214,3 +216,12 @@ def scaler(scale=65536.0, growth_interval=2000):
 
 def scaler_update(s, overflow):
     lib().orc_scaler_update(C.byref(s), int(bool(overflow)))
+
+
+def min_link_bytes(used, budgets_in_chunks, start_resident):
+    """Brute-force least link bytes of the ADAM scan over len(budgets) steps (tiny cases only)."""
+    used = np.ascontiguousarray(used, dtype=np.uint64)
+    b = np.ascontiguousarray(budgets_in_chunks, dtype=np.uint64)
+    st = np.ascontiguousarray(start_resident, dtype=np.uint8)
+    assert used.size * b.size <= 24
+    return int(lib().orc_min_link_bytes(_ptr(used), used.size, _ptr(b), b.size, _ptr(st)))

@@ -375,3 +375,37 @@ void orc_scaler_update(orc_scaler *s, uint32_t overflow)
         }
     }
 }
+
+/* ------------------------------------------------------------------ */
+/* Placement of optimizer-state chunks (Sec. "Device-aware Operator    */
+/* Placement") for the ADAM scan, by brute force: over T steps with    */
+/* HBM budgets budget[t] (in chunks), every assignment of every chunk  */
+/* to HBM or host after each step is tried (n_chunks*T <= 24 bits).    */
+/* A chunk that is on the host before a step is read over the link     */
+/* (12*used bytes), one that is on the host after it is written over   */
+/* the link (12*used bytes).  start[k] = 1 if chunk k starts in HBM.   */
+/* Returns the least total link bytes of any valid assignment.         */
+/* ------------------------------------------------------------------ */
+uint64_t orc_min_link_bytes(const uint64_t *used, uint64_t n_chunks, const uint64_t *budget, uint64_t T,
+                            const uint8_t *start)
+{
+    uint64_t best = UINT64_MAX;
+    const uint64_t bits = n_chunks * T;
+    for (uint64_t a = 0; a < (1ull << bits); a++) {       /* bit (t*n + k) = chunk k in HBM after step t */
+        uint64_t cost = 0;
+        int ok = 1;
+        for (uint64_t t = 0; t < T && ok; t++) {
+            uint64_t resident = 0;
+            for (uint64_t k = 0; k < n_chunks; k++) {
+                int after = (int)((a >> (t * n_chunks + k)) & 1u);
+                int before = t == 0 ? start[k] : (int)((a >> ((t - 1) * n_chunks + k)) & 1u);
+                resident += (uint64_t)after;
+                if (!before) cost += 12 * used[k];
+                if (!after) cost += 12 * used[k];
+            }
+            if (resident > budget[t]) ok = 0;
+        }
+        if (ok && cost < best) best = cost;
+    }
+    return best;
+}

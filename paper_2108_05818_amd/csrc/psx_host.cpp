@@ -103,3 +103,69 @@ extern "C" int32_t psx_loss_scale_update(psx_scaler *s, uint32_t overflow) {
     }
     return PSX_OK;
 }
+
+// ---------------------------------------------------------------------------
+// Placement of optimizer-state chunks for the ADAM stage and chunk-size search.
+// ---------------------------------------------------------------------------
+
+// A resident chunk costs 12*chunk_elems bytes of HBM whatever its fill; a
+// host-resident chunk costs 12*used bytes on the link in each direction at
+// every step.  So the chunks worth keeping are the fullest ones.  The order
+// (fill descending, index ascending) does not depend on the budget, which
+// makes the resident sets for growing budgets nested: when the budget moves,
+// only chunks at the margin change residence.
+extern "C" int32_t psx_plan_residency(const uint64_t *used, size_t n_chunks, uint64_t chunk_elems,
+                                      uint64_t hbm_budget_bytes, uint8_t *loc, uint64_t *host_elems) {
+    if (n_chunks != 0 && (used == nullptr || loc == nullptr)) return psx::fail(PSX_EINVAL, "psx_plan_residency: NULL array");
+    if (chunk_elems == 0) return psx::fail(PSX_EINVAL, "psx_plan_residency: chunk_elems is 0");
+    for (size_t k = 0; k < n_chunks; k++)
+        if (used[k] > chunk_elems) return psx::fail(PSX_EINVAL, "psx_plan_residency: used[%zu] exceeds the chunk", k);
+    const uint64_t per_chunk = 12ull * chunk_elems;
+    uint64_t room = hbm_budget_bytes / per_chunk;             // chunks that fit
+    if (room > n_chunks) room = n_chunks;
+    for (size_t k = 0; k < n_chunks; k++) loc[k] = PSX_LOC_HOST;
+    uint64_t streamed = 0;
+    for (size_t k = 0; k < n_chunks; k++) streamed += used[k];
+    // pick the `room` fullest chunks; n_chunks is a few hundred, a selection loop is enough
+    for (uint64_t r = 0; r < room; r++) {
+        size_t best = n_chunks;
+        for (size_t k = 0; k < n_chunks; k++)
+            if (loc[k] == PSX_LOC_HOST && (best == n_chunks || used[k] > used[best])) best = k;
+        if (best == n_chunks) break;
+        loc[best] = PSX_LOC_HBM;
+        streamed -= used[best];
+    }
+    if (host_elems != nullptr) *host_elems = streamed;
+    return PSX_OK;
+}
+
+extern "C" int32_t psx_chunk_size_search(const uint64_t *numel, size_t n, uint64_t lo, uint64_t hi, uint64_t step,
+                                         uint32_t flags, uint64_t max_model_data_bytes, uint64_t *best_chunk_elems,
+                                         double *best_util, size_t *best_n_chunks) {
+    if (best_chunk_elems == nullptr) return psx::fail(PSX_EINVAL, "psx_chunk_size_search: best_chunk_elems is NULL");
+    if (lo == 0 || step == 0 || hi < lo) return psx::fail(PSX_EINVAL, "psx_chunk_size_search: need 0 < lo <= hi and step > 0");
+    if (n != 0 && numel == nullptr) return psx::fail(PSX_EINVAL, "psx_chunk_size_search: numel is NULL");
+    uint64_t total = 0;
+    for (size_t i = 0; i < n; i++) total += numel[i];
+    bool found = false;
+    double util_best = -1.0;
+    uint64_t c_best = 0;
+    size_t n_best = 0;
+    for (uint64_t c = lo; c <= hi; c += step) {
+        size_t nch = 0;
+        const int32_t rc = psx_chunk_layout(numel, n, c, flags & PSX_LAYOUT_STRICT, nullptr, nullptr, 0, &nch);
+        if (rc == PSX_ETOOLARGE) { if (hi - c < step) break; continue; }   // a tensor does not fit this size
+        if (rc != PSX_OK) return rc;
+        // the four chunk lists take 14 bytes per element of chunk capacity
+        const long double bytes = 14.0L * (long double)nch * (long double)c;
+        if (max_model_data_bytes != 0 && bytes > (long double)max_model_data_bytes) { if (hi - c < step) break; continue; }
+        const double util = (double)((long double)total / ((long double)nch * (long double)c));
+        if (!found || util > util_best) { found = true; util_best = util; c_best = c; n_best = nch; }
+        if (hi - c < step) break;                                            // also guards the += against overflow
+    }
+    if (!found) return psx::fail(PSX_ETOOLARGE, "psx_chunk_size_search: no chunk size in the range holds the model");
+    *best_chunk_elems = c_best;
+    if (best_util) *best_util = util_best;
+    if (best_n_chunks) *best_n_chunks = n_best;
+    return PSX_OK;
+}

@@ -26,7 +26,8 @@ EXPORTS = [
     "psx_last_error", "psx_chunk_layout", "psx_ctx_create", "psx_ctx_destroy", "psx_pack", "psx_unpack",
     "psx_overflow_check", "psx_overflow_reset", "psx_overflow_read", "psx_chunk_adam_step",
     "psx_loss_scale_update", "psx_ctx_set_tuning", "psx_ctx_set_profiling", "psx_ctx_get_timing",
-    "psx_copy_bytes", "psx_measure_link", "psx_pinned_alloc", "psx_pinned_free",
+    "psx_copy_bytes", "psx_measure_link", "psx_pinned_alloc", "psx_pinned_free", "psx_plan_residency",
+    "psx_chunk_size_search",
 ]
 
 
@@ -106,6 +107,9 @@ def lib():
         "psx_measure_link": [vp, u64, u32, C.POINTER(psx_link_rates)],
         "psx_pinned_alloc": [u64, C.POINTER(vp)],
         "psx_pinned_free": [vp],
+        "psx_plan_residency": [vp, sz, u64, u64, vp, C.POINTER(u64)],
+        "psx_chunk_size_search": [vp, sz, u64, u64, u64, u32, u64, C.POINTER(u64), C.POINTER(C.c_double),
+                                  C.POINTER(sz)],
     }
     for name, args in sigs.items():
         f = getattr(L, name)
@@ -292,3 +296,23 @@ class PinnedF32:
             self.np = None
             psx_pinned_free(self.addr)
             self.addr = 0
+
+
+def psx_plan_residency(used, chunk_elems, hbm_budget_bytes):
+    """-> (loc list of PSX_LOC_*, host_elems)."""
+    n = len(used)
+    u = (C.c_uint64 * max(n, 1))(*used)
+    loc = (C.c_uint8 * max(n, 1))()
+    host = C.c_uint64(0)
+    _ok(lib().psx_plan_residency(u, n, chunk_elems, hbm_budget_bytes, loc, C.byref(host)))
+    return list(loc)[:n], host.value
+
+
+def psx_chunk_size_search(numel, lo, hi, step, flags=0, max_model_data_bytes=0):
+    """-> (best chunk_elems, utilisation, n_chunks)."""
+    n = len(numel)
+    arr = (C.c_uint64 * max(n, 1))(*numel)
+    best, util, nch = C.c_uint64(0), C.c_double(0), C.c_size_t(0)
+    _ok(lib().psx_chunk_size_search(arr, n, lo, hi, step, flags, max_model_data_bytes, C.byref(best),
+                                    C.byref(util), C.byref(nch)))
+    return best.value, util.value, nch.value

@@ -1,4 +1,4 @@
-"""GPU parity at BASELINE's full sizes, in the launch configuration bench.py times.
+"""GPU parity at the full sizes of the benchmark workloads, in the launch configuration bench.py times.
 The oracle cannot run 10^9 elements in seconds, so it runs free on a sample of
 whole chunks (first, last, the one holding the tail of the oversized embedding,
 the emptiest, random others), fed with the same seeded tensors; sampled chunks
