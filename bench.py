@@ -37,6 +37,7 @@ def parse():
     ap.add_argument("--workload", default="gpt1b", choices=["gpt1b", "tiny", "gpt12b"])
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (shape-preserving scale-down)")
     ap.add_argument("--host-fraction", type=float, default=-1.0, help="share of chunks whose fp32 states live in pinned host memory")
+    ap.add_argument("--cpu-share", type=float, default=0.0, help="share of the host-resident chunks updated by the host cores instead of the GPU")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="also launch psx_copy_bytes once over this many MiB (a plain copy of known size, "
@@ -52,10 +53,12 @@ class State:
     pass
 
 
-def setup(w, dev, host_fraction=0.0, staging_tile_elems=4 << 20, staging_slots=3, keep_params="all"):
+def setup(w, dev, host_fraction=0.0, staging_tile_elems=4 << 20, staging_slots=3, keep_params="all", cpu_share=0.0):
     """Allocate chunk lists and seeded inputs on the device (and pinned host memory for
     host-resident chunks); pack the fp32 params tensor by tensor; m = v = 0.
-    keep_params: "all" keeps every fp32 source tensor, an int keeps only the first that many."""
+    keep_params: "all" keeps every fp32 source tensor, an int keeps only the first that many.
+    cpu_share: share of the host-resident chunks that the host cores update (PSX_EXEC_CPU); the rest of
+    them is updated by the GPU over the link."""
     import torch
     from paper_2108_05818_amd import psx
     from paper_2108_05818_amd import workloads as W
@@ -67,6 +70,8 @@ def setup(w, dev, host_fraction=0.0, staging_tile_elems=4 << 20, staging_slots=3
     st.nch = len(st.used)
     n_host = int(round(host_fraction * st.nch))
     st.n_host = n_host
+    n_cpu = int(round(cpu_share * n_host))
+    st.n_cpu = n_cpu
     st.ctx = psx.psx_ctx_create(max_chunks=st.nch, max_tensors=len(w.numel),
                                 staging_tile_elems=staging_tile_elems if n_host else 0, staging_slots=staging_slots)
     C = st.C
@@ -107,7 +112,8 @@ def setup(w, dev, host_fraction=0.0, staging_tile_elems=4 << 20, staging_slots=3
             s.update(p32=st.p32[k], m=st.m[k], v=st.v[k], loc_in=psx.PSX_LOC_HBM, loc_out=psx.PSX_LOC_HBM)
         else:
             s.update(p32_host=st.host[k][0], m_host=st.host[k][1], v_host=st.host[k][2],
-                     loc_in=psx.PSX_LOC_HOST, loc_out=psx.PSX_LOC_HOST)
+                     loc_in=psx.PSX_LOC_HOST, loc_out=psx.PSX_LOC_HOST,
+                     exec=psx.PSX_EXEC_CPU if k >= st.nch - n_cpu else psx.PSX_EXEC_GPU)
         specs.append(s)
     st.chunks = psx.make_chunks(specs)
     st.t_ptrs = psx.ptr_array(st.g_t)
@@ -226,7 +232,7 @@ def main():
     host_fraction = w.host_fraction if a.host_fraction < 0 else a.host_fraction
     # the fp32 source tensors are needed again only by the oracle leg, and only the first few of them
     st = setup(w, dev, host_fraction, a.staging_tile, a.staging_slots,
-               keep_params=0 if a.no_cpu_baseline else CPU_BASELINE_TENSORS)
+               keep_params=0 if a.no_cpu_baseline else CPU_BASELINE_TENSORS, cpu_share=a.cpu_share)
     tune_keys = {"bpc": psx.PSX_TUNE_ADAM_BLOCKS_PER_CU, "unroll": psx.PSX_TUNE_ADAM_UNROLL,
                  "nt": psx.PSX_TUNE_NONTEMPORAL, "cbpc": psx.PSX_TUNE_COPY_BLOCKS_PER_CU,
                  "threads": psx.PSX_TUNE_ADAM_THREADS, "wg": psx.PSX_TUNE_ADAM_WG_PER_CU,
@@ -278,7 +284,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "n_elems": n_elems, "n_tensors": len(w.numel), "chunk_elems": w.chunk_elems,
-                   "n_chunks": st.nch, "host_resident_chunks": st.n_host, "loss_scale": w.loss_scale,
+                   "n_chunks": st.nch, "host_resident_chunks": st.n_host, "host_chunks_on_host_cores": st.n_cpu,
+                   "loss_scale": w.loss_scale,
                    "weight_decay": w.weight_decay, "fused_check": not a.separate_check, "skipped_steps": skipped},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
@@ -301,6 +308,9 @@ def main():
                             "measured_peak": peak,
                             "frac": h2d / max(r.h2d_alone, r.d2h_alone) if h2d else None,
                             "frac_of_copies_both_at_once": h2d / r.each_way_both if h2d else None,
+                            "host_cores": {"elems": int(tm.cpu_elems), "threads": int(tm.cpu_threads), "ms": float(tm.cpu_ms),
+                                           "gelem_s": tm.cpu_elems / (tm.cpu_ms * 1e-3) / 1e9 if tm.cpu_ms else None},
+                            "host_part_gelem_s": (tm.spill_elems + tm.cpu_elems) / link_s / 1e9 if link_s else None,
                             "spill_elems": int(tm.spill_elems), "spill_ms": phase["spill_ms"],
                             "spill_gelem_s": tm.spill_elems / link_s / 1e9 if link_s else None}
     print(json.dumps(out))

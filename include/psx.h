@@ -181,6 +181,11 @@ typedef struct psx_adam_hyper {
 #define PSX_LOC_HBM  0u   /* fp32 states in device memory  */
 #define PSX_LOC_HOST 1u   /* fp32 states in pinned host memory */
 
+#define PSX_EXEC_GPU 0u   /* the chunk is updated by the GPU kernel (host-resident: over the link)       */
+#define PSX_EXEC_CPU 1u   /* HOST -> HOST chunks only: updated in place by the host cores (the paper's    */
+                          /* placement for host-resident optimizer states): only the fp16 gradient tile   */
+                          /* (D2H) and the fp16 parameter tile (H2D) cross the link, 2 + 2 B/element      */
+
 /*
  * One chunk of the four lists.  g16 and p16 are always device memory; p16 may
  * equal g16 (the paper's chunk reuse: the gradient sits in the param fp16
@@ -207,7 +212,8 @@ typedef struct psx_chunk {
     uint64_t used;    /* elements in use (a prefix); the tail fragment is never touched */
     uint8_t loc_in;   /* PSX_LOC_* where the states are at entry */
     uint8_t loc_out;  /* PSX_LOC_* where they must be at exit    */
-    uint8_t reserved[6];
+    uint8_t exec;     /* PSX_EXEC_*; PSX_EXEC_CPU needs loc_in == loc_out == PSX_LOC_HOST */
+    uint8_t reserved[5];
 } psx_chunk;
 
 #define PSX_STEP_USE_FLAG    1u  /* skip the update if the context's overflow flag is set      */
@@ -217,7 +223,9 @@ typedef struct psx_chunk {
  * chunks[n_chunks]  host array.  All work is enqueued on `stream` and on the
  * context's two copy streams; on return `stream` has been made to wait for
  * them, so work enqueued on `stream` afterwards sees the finished step.
- * Asynchronous with respect to the host.
+ * Asynchronous with respect to the host, unless a chunk asks for PSX_EXEC_CPU: the GPU work is
+ * enqueued first and runs meanwhile, then the calling thread drives the host-core update (worker
+ * threads, AVX2 + F16C, same arithmetic and bits as the GPU kernel) and returns when it is done.
  * Skipped step (flag set): p32/m/v keep their bits (states that change
  * residence are still moved); p16 is left alone unless it aliases g16, in which
  * case it is rewritten with fp16(p32) so that the chunk holds parameters again.
@@ -268,6 +276,8 @@ int32_t psx_loss_scale_update(psx_scaler *s, uint32_t overflow);
 #define PSX_TUNE_HOST_MODE          8u
 #define PSX_TUNE_HOST_GRID          9u
 #define PSX_TUNE_HOST_UNROLL        10u
+#define PSX_TUNE_CPU_THREADS        11u  /* worker threads for PSX_EXEC_CPU chunks (default: min(cores, 16)) */
+#define PSX_TUNE_CPU_TILE_ELEMS     12u  /* elements per tile of the PSX_EXEC_CPU pipeline (multiple of 16)  */
 int32_t psx_ctx_set_tuning(psx_ctx *ctx, uint32_t key, int64_t value);
 
 /* Kernel timing with HIP events on the caller's stream (off by default). */
@@ -279,6 +289,9 @@ typedef struct psx_timing {
     uint64_t adam_elems;   /* elements the resident launch covered                         */
     uint64_t spill_elems;  /* elements of chunks with a host side                          */
     uint64_t h2d_bytes, d2h_bytes;  /* link bytes of the streamed part                     */
+    float cpu_ms;          /* last PSX_EXEC_CPU part: host wall time, first tile to last   */
+    uint32_t cpu_threads;  /* worker threads it used                                       */
+    uint64_t cpu_elems;    /* elements updated by the host cores                           */
 } psx_timing;
 int32_t psx_ctx_set_profiling(psx_ctx *ctx, int32_t on);
 /* Synchronises the recorded events, then fills *out (fields of phases not run are 0). */

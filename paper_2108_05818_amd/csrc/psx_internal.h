@@ -58,6 +58,8 @@ struct Tuning {
     int host_grid = 32;            // direct mode: persistent workgroups (256 threads) of the host launch
     int host_unroll = 1;           // direct mode: rows of 4 elements per thread
     int grid_override = 0;         // internal: absolute grid size of a launch (0: derive from blocks_per_cu)
+    int cpu_threads = 0;           // PSX_EXEC_CPU: worker threads (0: min(hardware threads, 16))
+    uint64_t cpu_tile_elems = 4u << 20;   // PSX_EXEC_CPU: elements per pipeline tile
 };
 
 // Elements per tile of the Adam kernel (threads x 4 elements x unroll).
@@ -83,5 +85,15 @@ hipError_t launch_copy(const CopySeg *segs_dev, uint32_t n_segs, uint64_t n_tile
 hipError_t launch_fill_u32(uint32_t *dst, uint64_t n, uint32_t value, hipStream_t s);
 hipError_t launch_copy_bytes(void *dst, const void *src, uint64_t n_bytes, const Tuning &t,
                              int n_cu, hipStream_t s);
+
+// ---- host-core Adam (psx_cpu.cpp) ----
+struct CpuPool;
+bool cpu_adam_supported();
+CpuPool *cpu_pool_create(int n_threads);
+void cpu_pool_destroy(CpuPool *p);
+int cpu_pool_size(const CpuPool *p);
+void cpu_adam_tile(CpuPool *pool, const uint16_t *g16, uint16_t *p16, float *p, float *m, float *v, size_t n,
+                   const AdamScalars &s);
+void cpu_recast_tile(CpuPool *pool, uint16_t *p16, const float *p, size_t n);
 
 }  // namespace psx

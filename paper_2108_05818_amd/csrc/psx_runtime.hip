@@ -4,6 +4,7 @@
 #include <chrono>
 #include <cmath>
 #include <cstring>
+#include <thread>
 #include <vector>
 
 #include "psx_internal.h"
@@ -13,6 +14,7 @@ using namespace psx;
 namespace {
 
 constexpr int kRing = 4;        // pinned upload buffers per table
+constexpr int kCpuSlots = 3;    // tiles in flight of the host-core pipeline
 
 // A descriptor table on the device, with the content last uploaded kept on the
 // host so that an unchanged table (the steady state of a training loop) is not
@@ -96,6 +98,16 @@ struct psx_ctx {
     uint64_t adam_elems = 0, spill_elems = 0, h2d_bytes = 0, d2h_bytes = 0;
     std::vector<AdamRun> runs;         // scratch for table building
     std::vector<CopySeg> segs;
+    // host-core execution (PSX_EXEC_CPU), allocated on first use
+    CpuPool *pool = nullptr;
+    hipStream_t aux = nullptr;         // H2D of the fp16 parameter tiles
+    uint16_t *cpu_g[kCpuSlots] = {nullptr, nullptr, nullptr};   // pinned: fp16 gradient tiles from the GPU
+    uint16_t *cpu_h[kCpuSlots] = {nullptr, nullptr, nullptr};   // pinned: fp16 parameter tiles for the GPU
+    hipEvent_t ev_cg[kCpuSlots] = {nullptr, nullptr, nullptr}, ev_ch[kCpuSlots] = {nullptr, nullptr, nullptr};
+    hipEvent_t ev_flag = nullptr, ev_cpu_end = nullptr;
+    uint64_t cpu_tile_alloc = 0;
+    float cpu_ms = 0.0f;
+    uint64_t cpu_elems = 0;
 };
 
 namespace {
@@ -207,6 +219,16 @@ extern "C" int32_t psx_ctx_destroy(psx_ctx *c) {
     if (c->flags_dev) note(hipFree(c->flags_dev), "hipFree(flags)");
     if (c->flags_host) note(hipHostFree(c->flags_host), "hipHostFree(flags)");
     if (c->staging) note(hipFree(c->staging), "hipFree(staging)");
+    if (c->pool) cpu_pool_destroy(c->pool);
+    if (c->aux) note(hipStreamDestroy(c->aux), "hipStreamDestroy");
+    for (int i = 0; i < kCpuSlots; i++) {
+        if (c->cpu_g[i]) note(hipHostFree(c->cpu_g[i]), "hipHostFree(cpu_g)");
+        if (c->cpu_h[i]) note(hipHostFree(c->cpu_h[i]), "hipHostFree(cpu_h)");
+        if (c->ev_cg[i]) note(hipEventDestroy(c->ev_cg[i]), "hipEventDestroy");
+        if (c->ev_ch[i]) note(hipEventDestroy(c->ev_ch[i]), "hipEventDestroy");
+    }
+    if (c->ev_flag) note(hipEventDestroy(c->ev_flag), "hipEventDestroy");
+    if (c->ev_cpu_end) note(hipEventDestroy(c->ev_cpu_end), "hipEventDestroy");
     if (c->h2d) note(hipStreamDestroy(c->h2d), "hipStreamDestroy");
     if (c->d2h) note(hipStreamDestroy(c->d2h), "hipStreamDestroy");
     for (hipEvent_t e : {c->ev_entry, c->ev_h2d_end, c->ev_d2h_end})
@@ -256,6 +278,15 @@ extern "C" int32_t psx_ctx_set_tuning(psx_ctx *c, uint32_t key, int64_t value) {
             if (value != 1 && value != 2 && value != 4) return fail(PSX_EINVAL, "host unroll must be 1, 2 or 4");
             c->tune.host_unroll = (int)value;
             break;
+        case PSX_TUNE_CPU_THREADS:
+            if (value < 0 || value > 256) return fail(PSX_EINVAL, "cpu threads must be 0..256");
+            if (c->pool && (int)value != c->tune.cpu_threads) { cpu_pool_destroy(c->pool); c->pool = nullptr; }
+            c->tune.cpu_threads = (int)value;
+            break;
+        case PSX_TUNE_CPU_TILE_ELEMS:
+            if (value < 16 || value % 16 != 0 || value > (1ll << 28)) return fail(PSX_EINVAL, "cpu tile must be a multiple of 16 in 16..2^28");
+            c->tune.cpu_tile_elems = (uint64_t)value;
+            break;
         case PSX_TUNE_ADAM_THREADS:
             if (value != 64 && value != 256) return fail(PSX_EINVAL, "adam threads must be 64 or 256");
             c->tune.adam_threads = (int)value;
@@ -293,6 +324,9 @@ extern "C" int32_t psx_ctx_get_timing(psx_ctx *c, psx_timing *out) {
     out->spill_elems = c->spill_elems;
     out->h2d_bytes = c->h2d_bytes;
     out->d2h_bytes = c->d2h_bytes;
+    out->cpu_ms = c->cpu_ms;
+    out->cpu_threads = c->pool ? (uint32_t)cpu_pool_size(c->pool) : 0u;
+    out->cpu_elems = c->cpu_elems;
     return PSX_OK;
 }
 
@@ -541,6 +575,52 @@ int32_t prepare_scalars(const psx_adam_hyper *h, AdamScalars *s) {
     return PSX_OK;
 }
 
+// Resources of the host-core path: worker pool, a stream for the fp16 parameter uploads, pinned
+// staging for fp16 gradient and parameter tiles, events.
+int32_t ensure_cpu(psx_ctx *c) {
+    if (c->pool == nullptr) {
+        int n = c->tune.cpu_threads;
+        if (n <= 0) {
+            n = (int)std::thread::hardware_concurrency();
+            if (n <= 0) n = 1;
+            if (n > 16) n = 16;
+        }
+        c->pool = cpu_pool_create(n);
+    }
+    if (c->aux == nullptr) {
+        PSX_HIP(hipStreamCreateWithFlags(&c->aux, hipStreamNonBlocking));
+        PSX_HIP(hipEventCreateWithFlags(&c->ev_flag, hipEventDisableTiming));
+        PSX_HIP(hipEventCreateWithFlags(&c->ev_cpu_end, hipEventDisableTiming));
+        for (int i = 0; i < kCpuSlots; i++) {
+            PSX_HIP(hipEventCreateWithFlags(&c->ev_cg[i], hipEventDisableTiming));
+            PSX_HIP(hipEventCreateWithFlags(&c->ev_ch[i], hipEventDisableTiming));
+        }
+    }
+    if (c->cpu_tile_alloc < c->tune.cpu_tile_elems) {
+        PSX_HIP(hipDeviceSynchronize());
+        for (int i = 0; i < kCpuSlots; i++) {
+            if (c->cpu_g[i]) PSX_HIP(hipHostFree(c->cpu_g[i]));
+            if (c->cpu_h[i]) PSX_HIP(hipHostFree(c->cpu_h[i]));
+            c->cpu_g[i] = c->cpu_h[i] = nullptr;
+        }
+        c->cpu_tile_alloc = 0;
+        for (int i = 0; i < kCpuSlots; i++) {
+            PSX_HIP(hipHostMalloc(reinterpret_cast<void **>(&c->cpu_g[i]), c->tune.cpu_tile_elems * 2, hipHostMallocDefault));
+            PSX_HIP(hipHostMalloc(reinterpret_cast<void **>(&c->cpu_h[i]), c->tune.cpu_tile_elems * 2, hipHostMallocDefault));
+        }
+        c->cpu_tile_alloc = c->tune.cpu_tile_elems;
+    }
+    return PSX_OK;
+}
+
+struct CpuTile {
+    const uint16_t *g16;   // device
+    uint16_t *p16;         // device
+    float *p, *m, *v;      // pinned host, updated in place
+    uint64_t n;
+    bool alias;
+};
+
 struct SpillTile {
     size_t run;            // index into the table (its AdamRun)
     const float *src[3];   // host sources (H2D) or NULL
@@ -581,10 +661,17 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
             if (!ch.p32 || !ch.m || !ch.v) return fail(PSX_EINVAL, "psx_chunk_adam_step: chunk %zu needs device p32/m/v", k);
             if (!aligned16(ch.p32) || !aligned16(ch.m) || !aligned16(ch.v)) return fail(PSX_EALIGN, "psx_chunk_adam_step: chunk %zu device states not 16-byte aligned", k);
         }
+        if (ch.exec > PSX_EXEC_CPU) return fail(PSX_EINVAL, "psx_chunk_adam_step: chunk %zu has a bad exec value %u", k, ch.exec);
+        if (ch.exec == PSX_EXEC_CPU) {
+            if (ch.loc_in != PSX_LOC_HOST || ch.loc_out != PSX_LOC_HOST)
+                return fail(PSX_EINVAL, "psx_chunk_adam_step: chunk %zu: PSX_EXEC_CPU needs a chunk that stays on the host", k);
+            if (!cpu_adam_supported()) return fail(PSX_EINVAL, "psx_chunk_adam_step: PSX_EXEC_CPU needs a host CPU with AVX2 and F16C");
+        }
         if (host_side) {
             if (!ch.p32_host || !ch.m_host || !ch.v_host) return fail(PSX_EINVAL, "psx_chunk_adam_step: chunk %zu needs pinned p32/m/v", k);
             if (!aligned16(ch.p32_host) || !aligned16(ch.m_host) || !aligned16(ch.v_host)) return fail(PSX_EALIGN, "psx_chunk_adam_step: chunk %zu host states not 16-byte aligned", k);
-            const bool staged = !(c->tune.host_mode == 1 && ch.loc_in == PSX_LOC_HOST && ch.loc_out == PSX_LOC_HOST);
+            const bool staged = ch.exec != PSX_EXEC_CPU &&
+                                !(c->tune.host_mode == 1 && ch.loc_in == PSX_LOC_HOST && ch.loc_out == PSX_LOC_HOST);
             if (staged && T == 0) return fail(PSX_ENOSTAGING, "psx_chunk_adam_step: chunk %zu is host-resident but the context has no staging", k);
         }
     }
@@ -620,6 +707,8 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
     const size_t n_check = c->runs.size() - n_res - n_recast;
 
     std::vector<SpillTile> tiles;
+    std::vector<CpuTile> cpu_tiles;
+    uint64_t cpu_elems = 0;
     uint64_t spill_elems = 0, h2d_bytes = 0, d2h_bytes = 0;
     uint64_t slot_counter = 0;
     const bool direct = c->tune.host_mode == 1;
@@ -627,6 +716,22 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
         const psx_chunk &ch = chunks[k];
         if (ch.used == 0 || (ch.loc_in == PSX_LOC_HBM && ch.loc_out == PSX_LOC_HBM)) continue;
         const bool in_host = ch.loc_in == PSX_LOC_HOST, out_host = ch.loc_out == PSX_LOC_HOST;
+        if (ch.exec == PSX_EXEC_CPU) {                // updated by the host cores, see the end of this function
+            const uint64_t ct = c->tune.cpu_tile_elems;
+            for (uint64_t off = 0; off < ch.used; off += ct) {
+                CpuTile t;
+                t.g16 = static_cast<const uint16_t *>(ch.g16) + off;
+                t.p16 = static_cast<uint16_t *>(ch.p16) + off;
+                t.p = static_cast<float *>(ch.p32_host) + off;
+                t.m = static_cast<float *>(ch.m_host) + off;
+                t.v = static_cast<float *>(ch.v_host) + off;
+                t.n = ch.used - off < ct ? ch.used - off : ct;
+                t.alias = ch.g16 == ch.p16;
+                cpu_tiles.push_back(t);
+            }
+            cpu_elems += ch.used;
+            continue;
+        }
         spill_elems += ch.used;
         if (direct && in_host && out_host) {          // handled below: the kernel works on the host buffers
             h2d_bytes += 3 * ch.used * sizeof(float);
@@ -673,14 +778,14 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
     if (direct) {
         for (size_t k = 0; k < n_chunks; k++) {
             const psx_chunk &ch = chunks[k];
-            if (ch.used == 0 || ch.loc_in != PSX_LOC_HOST || ch.loc_out != PSX_LOC_HOST) continue;
+            if (ch.used == 0 || ch.loc_in != PSX_LOC_HOST || ch.loc_out != PSX_LOC_HOST || ch.exec == PSX_EXEC_CPU) continue;
             direct_tiles += push_run(c->runs, ch.g16, ch.p16, ch.p32_host, ch.m_host, ch.v_host, ch.used, direct_tiles, direct_tile, (uint32_t)k);
         }
         n_direct = c->runs.size() - direct_off;
         if (use_flag)
             for (size_t k = 0; k < n_chunks; k++) {
                 const psx_chunk &ch = chunks[k];
-                if (ch.used == 0 || ch.loc_in != PSX_LOC_HOST || ch.loc_out != PSX_LOC_HOST || ch.g16 != ch.p16) continue;
+                if (ch.used == 0 || ch.loc_in != PSX_LOC_HOST || ch.loc_out != PSX_LOC_HOST || ch.g16 != ch.p16 || ch.exec == PSX_EXEC_CPU) continue;
                 direct_recast_tiles += push_run(c->runs, ch.g16, ch.p16, ch.p32_host, ch.m_host, ch.v_host, ch.used, direct_recast_tiles, recast_tile, (uint32_t)k);
             }
         n_direct_recast = c->runs.size() - direct_off - n_direct;
@@ -699,13 +804,21 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
     }
 
     // ---- the side streams may start once earlier work on the caller's stream (and the check) is done
-    const bool any_side = !tiles.empty() || n_direct != 0;
+    const bool any_cpu = !cpu_tiles.empty();
+    if (any_cpu && (rc = ensure_cpu(c)) != PSX_OK) return rc;
+    const bool any_side = !tiles.empty() || n_direct != 0 || any_cpu;
     c->t_spill.valid = false;
     if (any_side) {
         PSX_HIP(hipEventRecord(c->ev_entry, s));
         PSX_HIP(hipStreamWaitEvent(c->h2d, c->ev_entry, 0));
         PSX_HIP(hipStreamWaitEvent(c->d2h, c->ev_entry, 0));
+        if (any_cpu) PSX_HIP(hipStreamWaitEvent(c->aux, c->ev_entry, 0));
         if (c->prof) PSX_HIP(hipEventRecord(c->t_spill.a, c->h2d));
+    }
+    // the host cores need the flag's value: fetch it now, ahead of the resident launch
+    if (any_cpu && use_flag) {
+        PSX_HIP(hipMemcpyAsync(c->flags_host, c->flags_dev, sizeof(uint32_t), hipMemcpyDeviceToHost, s));
+        PSX_HIP(hipEventRecord(c->ev_flag, s));
     }
 
     // ---- HBM-resident chunks: one launch over all of them
@@ -758,6 +871,54 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
         } else {
             PSX_HIP(hipEventRecord(c->ev_free[e], s));
         }
+    }
+    // ---- host-resident chunks executed by the host cores: everything above is already running on the GPU;
+    // this thread now pipelines  D2H fp16 gradient tile -> update of p/m/v in place -> H2D fp16 parameter tile
+    c->cpu_elems = cpu_elems;
+    c->cpu_ms = 0.0f;
+    if (any_cpu) {
+        bool skip = false;
+        if (use_flag) {
+            PSX_HIP(hipEventSynchronize(c->ev_flag));
+            skip = c->flags_host[0] != 0;
+        }
+        if (skip) {                                   // nothing to update; aliased fp16 chunks get their params back
+            size_t w = 0;
+            for (size_t i = 0; i < cpu_tiles.size(); i++)
+                if (cpu_tiles[i].alias) cpu_tiles[w++] = cpu_tiles[i];
+            cpu_tiles.resize(w);
+        }
+        PSX_HIP(hipEventSynchronize(c->ev_cpu_end));   // the previous call's uploads have left the staging
+        const auto t0 = std::chrono::steady_clock::now();
+        const size_t nt = cpu_tiles.size();
+        size_t issued = 0;
+        auto fetch = [&](size_t i) -> int32_t {
+            const int slot = (int)(i % kCpuSlots);
+            PSX_HIP(hipMemcpyAsync(c->cpu_g[slot], cpu_tiles[i].g16, cpu_tiles[i].n * 2, hipMemcpyDeviceToHost, c->d2h));
+            PSX_HIP(hipEventRecord(c->ev_cg[slot], c->d2h));
+            return PSX_OK;
+        };
+        if (!skip)
+            for (; issued < nt && issued < (size_t)kCpuSlots; issued++)
+                if ((rc = fetch(issued)) != PSX_OK) return rc;
+        for (size_t i = 0; i < nt; i++) {
+            const CpuTile &t = cpu_tiles[i];
+            const int slot = (int)(i % kCpuSlots);
+            if (!skip) PSX_HIP(hipEventSynchronize(c->ev_cg[slot]));            // gradient tile has arrived
+            if (i >= (size_t)kCpuSlots) PSX_HIP(hipEventSynchronize(c->ev_ch[slot]));   // parameter staging sent
+            if (!skip) cpu_adam_tile(c->pool, c->cpu_g[slot], c->cpu_h[slot], t.p, t.m, t.v, t.n, sc);
+            else cpu_recast_tile(c->pool, c->cpu_h[slot], t.p, t.n);
+            PSX_HIP(hipMemcpyAsync(t.p16, c->cpu_h[slot], t.n * 2, hipMemcpyHostToDevice, c->aux));
+            PSX_HIP(hipEventRecord(c->ev_ch[slot], c->aux));
+            if (!skip && issued < nt) {               // this slot's gradient staging is free again
+                if ((rc = fetch(issued)) != PSX_OK) return rc;
+                issued++;
+            }
+        }
+        PSX_HIP(hipEventRecord(c->ev_cpu_end, c->aux));
+        PSX_HIP(hipStreamWaitEvent(s, c->ev_cpu_end, 0));
+        any_d2h = true;
+        c->cpu_ms = std::chrono::duration<float, std::milli>(std::chrono::steady_clock::now() - t0).count();
     }
     if (any_side) {
         if (any_h2d) { PSX_HIP(hipEventRecord(c->ev_h2d_end, c->h2d)); PSX_HIP(hipStreamWaitEvent(s, c->ev_h2d_end, 0)); }

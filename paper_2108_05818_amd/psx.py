@@ -17,10 +17,12 @@ PSX_LAYOUT_STRICT = 1
 PSX_F16, PSX_F32 = 1, 2
 PSX_PACK_CHECK_OVERFLOW = 1
 PSX_LOC_HBM, PSX_LOC_HOST = 0, 1
+PSX_EXEC_GPU, PSX_EXEC_CPU = 0, 1
 PSX_STEP_USE_FLAG, PSX_STEP_CHECK_FIRST = 1, 2
 PSX_TUNE_ADAM_BLOCKS_PER_CU, PSX_TUNE_ADAM_UNROLL, PSX_TUNE_NONTEMPORAL, PSX_TUNE_COPY_BLOCKS_PER_CU = 1, 2, 3, 4
 PSX_TUNE_ADAM_THREADS, PSX_TUNE_ADAM_WG_PER_CU, PSX_TUNE_COPY_UNROLL = 5, 6, 7
 PSX_TUNE_HOST_MODE, PSX_TUNE_HOST_GRID, PSX_TUNE_HOST_UNROLL = 8, 9, 10
+PSX_TUNE_CPU_THREADS, PSX_TUNE_CPU_TILE_ELEMS = 11, 12
 
 EXPORTS = [
     "psx_last_error", "psx_chunk_layout", "psx_ctx_create", "psx_ctx_destroy", "psx_pack", "psx_unpack",
@@ -55,7 +57,7 @@ class psx_adam_hyper(C.Structure):
 class psx_chunk(C.Structure):
     _fields_ = [("g16", C.c_void_p), ("p16", C.c_void_p), ("p32", C.c_void_p), ("m", C.c_void_p), ("v", C.c_void_p),
                 ("p32_host", C.c_void_p), ("m_host", C.c_void_p), ("v_host", C.c_void_p), ("used", C.c_uint64),
-                ("loc_in", C.c_uint8), ("loc_out", C.c_uint8), ("reserved", C.c_uint8 * 6)]
+                ("loc_in", C.c_uint8), ("loc_out", C.c_uint8), ("exec", C.c_uint8), ("reserved", C.c_uint8 * 5)]
 
 
 class psx_scaler(C.Structure):
@@ -66,7 +68,8 @@ class psx_scaler(C.Structure):
 class psx_timing(C.Structure):
     _fields_ = [("pack_ms", C.c_float), ("check_ms", C.c_float), ("adam_ms", C.c_float), ("spill_ms", C.c_float),
                 ("adam_elems", C.c_uint64), ("spill_elems", C.c_uint64), ("h2d_bytes", C.c_uint64),
-                ("d2h_bytes", C.c_uint64)]
+                ("d2h_bytes", C.c_uint64), ("cpu_ms", C.c_float), ("cpu_threads", C.c_uint32),
+                ("cpu_elems", C.c_uint64)]
 
 
 class psx_link_rates(C.Structure):
@@ -226,6 +229,7 @@ def make_chunks(specs):
         a.used = int(s["used"])
         a.loc_in = int(s.get("loc_in", PSX_LOC_HBM))
         a.loc_out = int(s.get("loc_out", a.loc_in))
+        a.exec = int(s.get("exec", PSX_EXEC_GPU))
     return arr
 
 

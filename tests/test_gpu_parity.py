@@ -399,3 +399,67 @@ def test_bad_arguments_touch_nothing():
         assert cl.compare("after refused calls") == 0.0       # nothing was touched
     finally:
         psx.psx_ctx_destroy(ctx)
+
+
+# ---------------------------------------------------------------------------------- host-resident chunks on the host cores
+
+@pytest.mark.parametrize("wd,adamw", [(0.0, 0), (0.01, 0), (0.01, 1)])
+@pytest.mark.parametrize("alias", [False, True])
+def test_host_chunks_updated_by_the_host_cores(orc, alias, wd, adamw):
+    """PSX_EXEC_CPU: the paper's placement for host-resident optimizer states.  Same bits as the GPU kernel
+    and the oracle, mixed in one call with HBM-resident and GPU-updated host chunks; a skipped step too."""
+    ctx = psx.psx_ctx_create(max_chunks=64, max_tensors=16, staging_tile_elems=4096, staging_slots=3)
+    psx.psx_ctx_set_tuning(ctx, psx.PSX_TUNE_CPU_THREADS, 3)
+    psx.psx_ctx_set_tuning(ctx, psx.PSX_TUNE_CPU_TILE_ELEMS, 4096)
+    try:
+        used = [20000, 4096, 12289, 1, 4097, 0, 16384, 9007, 15]
+        loc = [(G, G), (H, H), (H, H), (H, H), (H, H), (H, H), (G, G), (H, H), (H, H)]
+        ex = [0, 1, 1, 1, 0, 1, 0, 1, 1]
+        Cn = 20000
+        cl = ChunkLists(used, Cn, alias=alias)
+        fill_state(cl, 9000, 65536.0, zero_mv=False)
+        cl.set("g16", 7, np.array([0, 0x8000, 1, 0x8001, 0x03FF, 0x7BFF, 0xFBFF, 0x0400], np.uint16))
+        host = []
+        for k in range(cl.n):
+            hs = None
+            if loc[k][0] == H:
+                hs = [psx.PinnedF32(Cn, fill=0.0) for _ in range(3)]
+                for hbuf, name in zip(hs, ("p32", "m", "v")):
+                    hbuf.np[...] = cl.np[name][k]
+                    getattr(cl, name)[k].view(torch.int32).fill_(0x0BADBEEF)
+            host.append(hs)
+        specs = cl.specs(loc=loc, host=host)
+        for s, e in zip(specs, ex):
+            s["exec"] = e
+
+        class HostView:                       # lets ChunkLists.compare read the pinned buffers
+            def __init__(self, b): self.b = b
+            def cpu(self): return self
+            def numpy(self): return self.b.np
+        where = [None if h is None else [HostView(b) for b in h] for h in host]
+        for t in (1, 2, 3):
+            if t == 3:                        # an overflow in a GPU-resident chunk skips the host-core update too
+                cl.set("g16", 0, np.array([0x7C00], np.uint16), at=19999)
+            hp = dict(lr=1e-3, weight_decay=wd, adamw_mode=adamw, step=t, loss_scale=65536.0)
+            psx.psx_chunk_adam_step(ctx, psx.make_chunks(specs), psx.make_hyper(**hp), psx.PSX_STEP_CHECK_FIRST)
+            flag, _ = psx.psx_overflow_read(ctx)
+            torch.cuda.synchronize()
+            assert flag == cl.oracle_step(orc, orc.hyper(**hp)) == int(t == 3)
+            assert cl.compare(f"t={t}", where=where) == 0.0
+            tm = psx.psx_ctx_get_timing(ctx)
+            assert tm.cpu_elems == sum(u for u, e in zip(used, ex) if e) and tm.cpu_threads == 3
+            assert tm.spill_elems == used[4]
+            if t < 3:
+                for k in range(cl.n):
+                    cl.set("g16", k, W.grads_f16_np(used[k], 9500 + 10 * k + t, 65536.0))
+        # asking for the host cores on a chunk that lives in HBM is refused
+        bad = cl.specs()
+        bad[0]["exec"] = psx.PSX_EXEC_CPU
+        with pytest.raises(psx.PsxError) as e:
+            psx.psx_chunk_adam_step(ctx, psx.make_chunks(bad), psx.make_hyper())
+        assert e.value.code == psx.PSX_EINVAL
+    finally:
+        psx.psx_ctx_destroy(ctx)
+        for hs in host:
+            for b in hs or []:
+                b.free()
