@@ -237,7 +237,9 @@ def main():
                  "nt": psx.PSX_TUNE_NONTEMPORAL, "cbpc": psx.PSX_TUNE_COPY_BLOCKS_PER_CU,
                  "threads": psx.PSX_TUNE_ADAM_THREADS, "wg": psx.PSX_TUNE_ADAM_WG_PER_CU,
                  "cunroll": psx.PSX_TUNE_COPY_UNROLL, "hostmode": psx.PSX_TUNE_HOST_MODE,
-                 "hostgrid": psx.PSX_TUNE_HOST_GRID, "hostunroll": psx.PSX_TUNE_HOST_UNROLL}
+                 "hostgrid": psx.PSX_TUNE_HOST_GRID, "hostunroll": psx.PSX_TUNE_HOST_UNROLL,
+                 "cputhreads": psx.PSX_TUNE_CPU_THREADS, "cputile": psx.PSX_TUNE_CPU_TILE_ELEMS,
+                 "cpuisa": psx.PSX_TUNE_CPU_ISA}
     for kv in filter(None, a.tune.split(",")):
         k, v = kv.split("=")
         psx.psx_ctx_set_tuning(st.ctx, tune_keys[k], int(v))

@@ -278,6 +278,7 @@ int32_t psx_loss_scale_update(psx_scaler *s, uint32_t overflow);
 #define PSX_TUNE_HOST_UNROLL        10u
 #define PSX_TUNE_CPU_THREADS        11u  /* worker threads for PSX_EXEC_CPU chunks (default: min(cores, 16)) */
 #define PSX_TUNE_CPU_TILE_ELEMS     12u  /* elements per tile of the PSX_EXEC_CPU pipeline (multiple of 16)  */
+#define PSX_TUNE_CPU_ISA            13u  /* PSX_EXEC_CPU vectors: 0 = widest the host has (AVX-512, else AVX2), 1 = AVX2 */
 int32_t psx_ctx_set_tuning(psx_ctx *ctx, uint32_t key, int64_t value);
 
 /* Kernel timing with HIP events on the caller's stream (off by default). */

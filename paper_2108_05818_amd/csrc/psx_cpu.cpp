@@ -4,7 +4,7 @@
 // off the host link, only fp16 gradients and fp16 parameters cross it).
 //
 // The arithmetic is the one printed in include/psx.h, in the same order, with
-// AVX2 + F16C: every vector instruction used here is IEEE-correct per lane
+// AVX2 + F16C (or AVX-512 where the host has it): every vector instruction used here is IEEE-correct per lane
 // (mul, add, sub, div, sqrt; no fused multiply-add is ever issued), fp16->fp32
 // is exact and fp32->fp16 rounds to nearest even, so the results equal the GPU
 // kernel's bit for bit.  MXCSR is set to round-to-nearest with denormals kept
@@ -159,9 +159,52 @@ __attribute__((target("avx2,f16c"))) static void recast_range_avx2(uint16_t *p16
     }
 }
 
-// One tile, split evenly (in multiples of 16 elements) over the pool.
+// The same with 16 lanes where the host has AVX-512 (F + BW + VL); the ragged end uses lane masks.
+template <int DM>
+__attribute__((target("avx512f,avx512bw,avx512vl"))) static void adam_range_avx512(const uint16_t *g16, uint16_t *p16,
+                                                                                  float *pp, float *pm, float *pv,
+                                                                                  size_t n, const AdamScalars &s) {
+    const __m512 inv_scale = _mm512_set1_ps(s.inv_scale), beta1 = _mm512_set1_ps(s.beta1),
+                 beta2 = _mm512_set1_ps(s.beta2), omb1 = _mm512_set1_ps(s.omb1), omb2 = _mm512_set1_ps(s.omb2),
+                 eps = _mm512_set1_ps(s.eps), wd = _mm512_set1_ps(s.wd), decay = _mm512_set1_ps(s.decay),
+                 c2 = _mm512_set1_ps(s.c2), step_size = _mm512_set1_ps(s.step_size);
+    for (size_t i = 0; i < n; i += 16) {
+        const size_t left = n - i;
+        const __mmask16 k = left >= 16 ? (__mmask16)0xFFFF : (__mmask16)((1u << left) - 1u);
+        const __m256i gh = _mm256_maskz_loadu_epi16(k, g16 + i);
+        __m512 p = _mm512_maskz_loadu_ps(k, pp + i);
+        __m512 m = _mm512_maskz_loadu_ps(k, pm + i);
+        __m512 v = _mm512_maskz_loadu_ps(k, pv + i);
+        __m512 g = _mm512_mul_ps(_mm512_cvtph_ps(gh), inv_scale);
+        if (DM == 1) g = _mm512_add_ps(g, _mm512_mul_ps(wd, p));
+        if (DM == 2) p = _mm512_mul_ps(p, decay);
+        m = _mm512_add_ps(_mm512_mul_ps(beta1, m), _mm512_mul_ps(omb1, g));
+        v = _mm512_add_ps(_mm512_mul_ps(beta2, v), _mm512_mul_ps(_mm512_mul_ps(omb2, g), g));
+        const __m512 den = _mm512_add_ps(_mm512_mul_ps(_mm512_sqrt_ps(v), c2), eps);
+        p = _mm512_sub_ps(p, _mm512_mul_ps(step_size, _mm512_div_ps(m, den)));
+        const __m256i h = _mm512_cvtps_ph(p, _MM_FROUND_TO_NEAREST_INT | _MM_FROUND_NO_EXC);
+        _mm512_mask_storeu_ps(pp + i, k, p);
+        _mm512_mask_storeu_ps(pm + i, k, m);
+        _mm512_mask_storeu_ps(pv + i, k, v);
+        _mm256_mask_storeu_epi16(p16 + i, k, h);
+    }
+}
+
+static bool have_avx512() {
+    return __builtin_cpu_supports("avx512f") && __builtin_cpu_supports("avx512bw") && __builtin_cpu_supports("avx512vl");
+}
+
+template <int DM>
+static void adam_range(bool wide, const uint16_t *g16, uint16_t *p16, float *p, float *m, float *v, size_t n,
+                       const AdamScalars &s) {
+    if (wide) adam_range_avx512<DM>(g16, p16, p, m, v, n, s);
+    else adam_range_avx2<DM>(g16, p16, p, m, v, n, s);
+}
+
+// One tile, split evenly (in multiples of 16 elements) over the pool.  isa: 0 = widest the host has, 1 = AVX2.
 void cpu_adam_tile(CpuPool *pool, const uint16_t *g16, uint16_t *p16, float *p, float *m, float *v, size_t n,
-                   const AdamScalars &s) {
+                   const AdamScalars &s, int isa) {
+    const bool wide = isa == 0 && have_avx512();
     const int nt = pool->size();
     const size_t per = ((n + nt - 1) / nt + 15) & ~(size_t)15;
     pool->parallel([&](int w) {
@@ -169,9 +212,9 @@ void cpu_adam_tile(CpuPool *pool, const uint16_t *g16, uint16_t *p16, float *p, 
         if (lo >= n) return;
         const size_t cnt = n - lo < per ? n - lo : per;
         switch (s.decay_mode) {
-            case 0: adam_range_avx2<0>(g16 + lo, p16 + lo, p + lo, m + lo, v + lo, cnt, s); break;
-            case 1: adam_range_avx2<1>(g16 + lo, p16 + lo, p + lo, m + lo, v + lo, cnt, s); break;
-            default: adam_range_avx2<2>(g16 + lo, p16 + lo, p + lo, m + lo, v + lo, cnt, s); break;
+            case 0: adam_range<0>(wide, g16 + lo, p16 + lo, p + lo, m + lo, v + lo, cnt, s); break;
+            case 1: adam_range<1>(wide, g16 + lo, p16 + lo, p + lo, m + lo, v + lo, cnt, s); break;
+            default: adam_range<2>(wide, g16 + lo, p16 + lo, p + lo, m + lo, v + lo, cnt, s); break;
         }
     });
 }

@@ -60,6 +60,7 @@ struct Tuning {
     int grid_override = 0;         // internal: absolute grid size of a launch (0: derive from blocks_per_cu)
     int cpu_threads = 0;           // PSX_EXEC_CPU: worker threads (0: min(hardware threads, 16))
     uint64_t cpu_tile_elems = 4u << 20;   // PSX_EXEC_CPU: elements per pipeline tile
+    int cpu_isa = 0;               // PSX_EXEC_CPU: 0 widest vectors the host has (AVX-512 or AVX2), 1 AVX2
 };
 
 // Elements per tile of the Adam kernel (threads x 4 elements x unroll).
@@ -93,7 +94,7 @@ CpuPool *cpu_pool_create(int n_threads);
 void cpu_pool_destroy(CpuPool *p);
 int cpu_pool_size(const CpuPool *p);
 void cpu_adam_tile(CpuPool *pool, const uint16_t *g16, uint16_t *p16, float *p, float *m, float *v, size_t n,
-                   const AdamScalars &s);
+                   const AdamScalars &s, int isa);
 void cpu_recast_tile(CpuPool *pool, uint16_t *p16, const float *p, size_t n);
 
 }  // namespace psx

@@ -283,6 +283,10 @@ extern "C" int32_t psx_ctx_set_tuning(psx_ctx *c, uint32_t key, int64_t value) {
             if (c->pool && (int)value != c->tune.cpu_threads) { cpu_pool_destroy(c->pool); c->pool = nullptr; }
             c->tune.cpu_threads = (int)value;
             break;
+        case PSX_TUNE_CPU_ISA:
+            if (value != 0 && value != 1) return fail(PSX_EINVAL, "cpu isa must be 0 (widest available) or 1 (AVX2)");
+            c->tune.cpu_isa = (int)value;
+            break;
         case PSX_TUNE_CPU_TILE_ELEMS:
             if (value < 16 || value % 16 != 0 || value > (1ll << 28)) return fail(PSX_EINVAL, "cpu tile must be a multiple of 16 in 16..2^28");
             c->tune.cpu_tile_elems = (uint64_t)value;
@@ -906,7 +910,7 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
             const int slot = (int)(i % kCpuSlots);
             if (!skip) PSX_HIP(hipEventSynchronize(c->ev_cg[slot]));            // gradient tile has arrived
             if (i >= (size_t)kCpuSlots) PSX_HIP(hipEventSynchronize(c->ev_ch[slot]));   // parameter staging sent
-            if (!skip) cpu_adam_tile(c->pool, c->cpu_g[slot], c->cpu_h[slot], t.p, t.m, t.v, t.n, sc);
+            if (!skip) cpu_adam_tile(c->pool, c->cpu_g[slot], c->cpu_h[slot], t.p, t.m, t.v, t.n, sc, c->tune.cpu_isa);
             else cpu_recast_tile(c->pool, c->cpu_h[slot], t.p, t.n);
             PSX_HIP(hipMemcpyAsync(t.p16, c->cpu_h[slot], t.n * 2, hipMemcpyHostToDevice, c->aux));
             PSX_HIP(hipEventRecord(c->ev_ch[slot], c->aux));

@@ -403,14 +403,15 @@ def test_bad_arguments_touch_nothing():
 
 # ---------------------------------------------------------------------------------- host-resident chunks on the host cores
 
-@pytest.mark.parametrize("wd,adamw", [(0.0, 0), (0.01, 0), (0.01, 1)])
+@pytest.mark.parametrize("wd,adamw,isa", [(0.0, 0, 0), (0.01, 0, 0), (0.01, 1, 0), (0.01, 0, 1), (0.01, 1, 1)])
 @pytest.mark.parametrize("alias", [False, True])
-def test_host_chunks_updated_by_the_host_cores(orc, alias, wd, adamw):
+def test_host_chunks_updated_by_the_host_cores(orc, alias, wd, adamw, isa):
     """PSX_EXEC_CPU: the paper's placement for host-resident optimizer states.  Same bits as the GPU kernel
     and the oracle, mixed in one call with HBM-resident and GPU-updated host chunks; a skipped step too."""
     ctx = psx.psx_ctx_create(max_chunks=64, max_tensors=16, staging_tile_elems=4096, staging_slots=3)
     psx.psx_ctx_set_tuning(ctx, psx.PSX_TUNE_CPU_THREADS, 3)
     psx.psx_ctx_set_tuning(ctx, psx.PSX_TUNE_CPU_TILE_ELEMS, 4096)
+    psx.psx_ctx_set_tuning(ctx, psx.PSX_TUNE_CPU_ISA, isa)      # 0: AVX-512 where the host has it; 1: AVX2
     try:
         used = [20000, 4096, 12289, 1, 4097, 0, 16384, 9007, 15]
         loc = [(G, G), (H, H), (H, H), (H, H), (H, H), (H, H), (G, G), (H, H), (H, H)]
