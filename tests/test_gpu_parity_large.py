@@ -342,3 +342,92 @@ def test_config5_shape_residency_changes_every_step(orc):
         for hs in host:
             for b in hs:
                 b.free()
+
+
+# ---------------------------------------------------------------------------------- sizes past 2^31, and empty calls
+
+def test_elements_beyond_two_to_the_31(orc):
+    """One chunk with more than 2^31 elements in use, and one tensor of that size running over three chunks:
+    every index in the kernels is 64-bit.  The oracle is run on windows at the start, across 2^31 and at the end."""
+    n = (1 << 31) + 1000
+    ctx = psx.psx_ctx_create(max_chunks=4, max_tensors=2)
+    try:
+        gen = torch.Generator(device=DEV)
+        gen.manual_seed(77)
+        g = torch.empty(n, dtype=torch.float16, device=DEV)
+        p = torch.empty(n, dtype=torch.float32, device=DEV)
+        step = 1 << 28
+        for lo in range(0, n, step):                                  # fill piecewise to keep temporaries small
+            hi = min(n, lo + step)
+            g[lo:hi] = (torch.randn(hi - lo, generator=gen, device=DEV) * 65.0).half()
+            p[lo:hi] = torch.randn(hi - lo, generator=gen, device=DEV) * 0.02
+        m = torch.zeros(n, dtype=torch.float32, device=DEV)
+        v = torch.zeros(n, dtype=torch.float32, device=DEV)
+        p16 = torch.zeros(n, dtype=torch.float16, device=DEV)
+        windows = [(0, 5000), ((1 << 31) - 3000, n), ((1 << 30) + 17, (1 << 30) + 4113), ((3 << 29) - 1, (3 << 29) + 2049)]
+        before = [(bits16(g[a:b]), f32(p[a:b])) for a, b in windows]
+        # overflow flag: clean, then an inf beyond 2^31
+        flag, per = psx.psx_overflow_check(ctx, [g], [n])
+        assert (flag, per) == (0, [0])
+        keep = g[(1 << 31) + 500].clone()
+        g[(1 << 31) + 500] = float("inf")
+        assert psx.psx_overflow_check(ctx, [g], [n]) == (1, [1])
+        assert psx.psx_overflow_check(ctx, [g], [(1 << 31) + 500]) == (0, [0])     # just outside the used prefix
+        g[(1 << 31) + 500] = keep
+        hp = dict(lr=1e-3, weight_decay=0.01, step=1, loss_scale=65536.0)
+        spec = [dict(g16=g, p16=p16, p32=p, m=m, v=v, used=n)]
+        psx.psx_chunk_adam_step(ctx, psx.make_chunks(spec), psx.make_hyper(**hp), psx.PSX_STEP_CHECK_FIRST)
+        torch.cuda.synchronize()
+        for (a, b), (g_np, p_np) in zip(windows, before):
+            k = b - a
+            om, ov, o16 = np.zeros(k, np.float32), np.zeros(k, np.float32), np.zeros(k, np.uint16)
+            op = p_np.copy()
+            orc.adam_chunk(g_np.copy(), o16, op, om, ov, k, orc.hyper(**hp))
+            assert f32(p[a:b]).tobytes() == op.tobytes() and f32(m[a:b]).tobytes() == om.tobytes()
+            assert f32(v[a:b]).tobytes() == ov.tobytes() and bits16(p16[a:b]).tobytes() == o16.tobytes()
+        # pack / unpack of a tensor with more than 2^31 elements over three chunks of 2^30
+        C = 1 << 30
+        slots, used = psx.psx_chunk_layout([5, n], C)
+        assert used == [5, C, C, 1000] and (slots[1].chunk, slots[1].offset) == (1, 0)
+        del m, v, p
+        chunks = [torch.zeros(C, dtype=torch.float16, device=DEV) for _ in range(4)]
+        five = torch.arange(5, dtype=torch.float16, device=DEV)
+        psx.psx_pack(ctx, psx.PSX_F16, [five, g], slots, chunks, C)
+        for (a, b) in windows:
+            lin = C + a                                              # the tensor starts at chunk 1, offset 0
+            got = torch.cat([chunks[(lin + i) // C][(lin + i) % C:(lin + i) % C + 1] for i in (0, b - a - 1)])
+            assert torch.equal(got.view(torch.int16), torch.stack([g[a], g[b - 1]]).view(torch.int16))
+        assert torch.equal(chunks[1].view(torch.int16), g[:C].view(torch.int16))
+        assert torch.equal(chunks[3][:1000].view(torch.int16), g[2 * C:].view(torch.int16)) and not chunks[3][1000:].any()
+        p16.zero_()
+        psx.psx_unpack(ctx, psx.PSX_F16, [torch.zeros(5, dtype=torch.float16, device=DEV), p16], slots, chunks, C)
+        torch.cuda.synchronize()
+        assert torch.equal(p16.view(torch.int16), g.view(torch.int16))
+    finally:
+        psx.psx_ctx_destroy(ctx)
+
+
+def test_empty_calls_do_nothing():
+    ctx = psx.psx_ctx_create(max_chunks=4, max_tensors=4)
+    try:
+        assert psx.psx_overflow_check(ctx, [], []) == (0, [])
+        psx.psx_chunk_adam_step(ctx, psx.make_chunks([]), psx.make_hyper(), psx.PSX_STEP_CHECK_FIRST, n_chunks=0)
+        slots, used = psx.psx_chunk_layout([], 64)
+        assert used == [0]
+        c = torch.full((64,), 7.0, dtype=torch.float16, device=DEV)
+        psx.psx_pack(ctx, psx.PSX_F16, [], slots, [c], 64, n=0)
+        psx.psx_unpack(ctx, psx.PSX_F16, [], slots, [c], 64, n=0)
+        # a list of empty tensors and a chunk with nothing in use
+        slots, used = psx.psx_chunk_layout([0, 0], 64)
+        e = torch.zeros(0, dtype=torch.float16, device=DEV)
+        psx.psx_pack(ctx, psx.PSX_F16, [e, e], slots, [c], 64)
+        z = torch.zeros(64, dtype=torch.float32, device=DEV)
+        spec = [dict(g16=c, p16=c, p32=z, m=z, v=z, used=0)]
+        psx.psx_chunk_adam_step(ctx, psx.make_chunks(spec), psx.make_hyper(), psx.PSX_STEP_CHECK_FIRST)
+        assert psx.psx_overflow_read(ctx, 1) == (0, [0])
+        torch.cuda.synchronize()
+        assert torch.all(c == 7.0) and not z.any()
+        r = psx.psx_measure_link(ctx, 16, 1)
+        assert r.h2d_alone > 1.0 and r.d2h_alone > 1.0 and r.each_way_both > 0.5
+    finally:
+        psx.psx_ctx_destroy(ctx)
