@@ -11,7 +11,7 @@ parameter set, every part of it in the HIP library behind include/psx.h:
   synchronises) and loss-scale update.
 Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps 20] [--warmup 3] [--workload gpt1b|tiny|gpt12b]
+  python bench.py [--gpus 1] [--steps 20] [--warmup 3] [--workload gpt1b|tiny|gpt12b|ragged]
 """
 import argparse
 import json
@@ -34,8 +34,9 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="gpt1b", choices=["gpt1b", "tiny", "gpt12b"])
+    ap.add_argument("--workload", default="gpt1b", choices=["gpt1b", "tiny", "gpt12b", "ragged"])
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (shape-preserving scale-down)")
+    ap.add_argument("--chunk-elems", type=int, default=0, help="override the chunk size (elements)")
     ap.add_argument("--host-fraction", type=float, default=-1.0, help="share of chunks whose fp32 states live in pinned host memory")
     ap.add_argument("--cpu-share", type=float, default=0.0, help="share of the host-resident chunks updated by the host cores instead of the GPU")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -75,16 +76,23 @@ def setup(w, dev, host_fraction=0.0, staging_tile_elems=4 << 20, staging_slots=3
     st.ctx = psx.psx_ctx_create(max_chunks=st.nch, max_tensors=len(w.numel),
                                 staging_tile_elems=staging_tile_elems if n_host else 0, staging_slots=staging_slots)
     C = st.C
-    st.p16 = [torch.zeros(C, dtype=torch.float16, device=dev) for _ in range(st.nch)]
-    st.g16 = [torch.zeros(C, dtype=torch.float16, device=dev) for _ in range(st.nch)]
-    # fp32 states: the first chunks in HBM, the last n_host chunks in pinned host memory
-    st.p32, st.m, st.v, st.host = [], [], [], []
     first_host = st.nch - n_host
+
+    def chunk_list(dtype, n):
+        """One chunk list = one arena, chunk k at offset k*C (the paper's ChunkLists: a list of chunks per
+        tensor type).  Besides being the natural layout it keeps the five streams of a chunk apart in
+        memory: p/m/v buffers of one chunk allocated back to back sit at power-of-two distances from each
+        other, which costs up to 13 % of the Adam kernel's bandwidth with small chunks."""
+        arena = torch.zeros(C * max(n, 1), dtype=dtype, device=dev)
+        return [arena[k * C:(k + 1) * C] for k in range(n)]
+    st.p16 = chunk_list(torch.float16, st.nch)
+    st.g16 = chunk_list(torch.float16, st.nch)
+    # fp32 states: the first chunks in HBM, the last n_host chunks in pinned host memory
+    p_list, m_list, v_list = (chunk_list(torch.float32, first_host) for _ in range(3))
+    st.p32, st.m, st.v, st.host = [], [], [], []
     for k in range(st.nch):
         if k < first_host:
-            st.p32.append(torch.zeros(C, dtype=torch.float32, device=dev))
-            st.m.append(torch.zeros(C, dtype=torch.float32, device=dev))
-            st.v.append(torch.zeros(C, dtype=torch.float32, device=dev))
+            st.p32.append(p_list[k]); st.m.append(m_list[k]); st.v.append(v_list[k])
             st.host.append(None)
         else:
             st.p32.append(None); st.m.append(None); st.v.append(None)
@@ -225,10 +233,15 @@ def main():
     dev = "cuda:0"
     if a.workload == "tiny":
         w = W.config1_tiny()
+    elif a.workload == "ragged":
+        w = W.config3_ragged()
     elif a.workload == "gpt12b":
         w = W.config4_gpt12b(a.layers or 40)
     else:
         w = W.config2_gpt1b(a.layers or 20)
+    if a.chunk_elems:
+        w.chunk_elems = a.chunk_elems
+        w.name += f"-C{a.chunk_elems}"
     host_fraction = w.host_fraction if a.host_fraction < 0 else a.host_fraction
     # the fp32 source tensors are needed again only by the oracle leg, and only the first few of them
     st = setup(w, dev, host_fraction, a.staging_tile, a.staging_slots,
@@ -277,7 +290,7 @@ def main():
     adam_bytes = ADAM_BYTES_PER_ELEM * adam_elems
     achieved = adam_bytes / (phase["adam_ms"] * 1e-3) / 1e9 if phase["adam_ms"] > 0 else 0.0
     traffic = read_traffic(os.path.join(ROOT, "profiles", "adam_kernel_gpt1b_hbm_traffic.txt")) \
-        if (a.workload == "gpt1b" and not a.layers and host_fraction == 0) else None
+        if (a.workload == "gpt1b" and not a.layers and not a.chunk_elems and host_fraction == 0) else None
     out = {
         "metric": "chunked Adam Gelem/s (whole hot path per step: layout + grad pack + overflow check + fused Adam + fp16 unpack + loss-scale update)",
         "value": n_elems / (ms * 1e-3) / 1e9,

@@ -70,17 +70,30 @@ constexpr uint64_t kRecastTileElems = (uint64_t)kThreads * 4u * 2u;
 constexpr uint64_t kCheckTileElems = (uint64_t)kThreads * 8u * 4u;   // 8192 fp16 per tile
 inline uint64_t copy_tile_bytes(const Tuning &t) { return (uint64_t)kThreads * 16u * (uint64_t)(t.copy_unroll == 1 ? 1 : 4); }
 
+// A section of a descriptor table on the device: n descriptors and, in a dense array of its own,
+// the first tile of each (what the kernels search to find the owner of a tile).
+struct RunView {
+    const AdamRun *runs;
+    const uint64_t *begins;
+    uint32_t n;
+};
+struct SegView {
+    const CopySeg *segs;
+    const uint64_t *begins;
+    uint32_t n;
+};
+
 // ---- launchers (psx_kernels.hip).  All enqueue on `s` and return the launch status. ----
-hipError_t launch_adam(const AdamRun *runs_dev, uint32_t n_runs, uint64_t n_tiles,
+hipError_t launch_adam(const RunView &rv, uint64_t n_tiles,
                        const AdamScalars &sc, const uint32_t *flag_dev, const Tuning &t,
                        int n_cu, hipStream_t s);
 // skipped step with p16 aliasing g16: p16 = fp16(p32), only when *flag_dev != 0
-hipError_t launch_recast_if_flag(const AdamRun *runs_dev, uint32_t n_runs, uint64_t n_tiles,
+hipError_t launch_recast_if_flag(const RunView &rv, uint64_t n_tiles,
                                  const uint32_t *flag_dev, const Tuning &t, int n_cu, hipStream_t s);
-hipError_t launch_check(const AdamRun *runs_dev, uint32_t n_runs, uint64_t n_tiles,
+hipError_t launch_check(const RunView &rv, uint64_t n_tiles,
                         uint32_t *flag_dev, uint32_t *per_chunk_dev, const Tuning &t, int n_cu,
                         hipStream_t s);
-hipError_t launch_copy(const CopySeg *segs_dev, uint32_t n_segs, uint64_t n_tiles,
+hipError_t launch_copy(const SegView &sv, uint64_t n_tiles,
                        uint32_t elem_size, uint32_t *flag_dev, uint32_t *per_chunk_dev,
                        const Tuning &t, int n_cu, hipStream_t s);
 hipError_t launch_fill_u32(uint32_t *dst, uint64_t n, uint32_t value, hipStream_t s);

@@ -73,6 +73,22 @@ int32_t table_upload(Table &t, const void *data, size_t bytes, hipStream_t s) {
     return PSX_OK;
 }
 
+// Uploads descriptors followed by the dense array of their first tiles; returns device pointers to both.
+template <typename D>
+int32_t upload_described(Table &t, const std::vector<D> &v, std::vector<unsigned char> &blob, hipStream_t s,
+                         const D **items, const uint64_t **begins) {
+    const size_t nd = v.size() * sizeof(D);
+    blob.resize(nd + v.size() * sizeof(uint64_t));
+    if (!v.empty()) memcpy(blob.data(), v.data(), nd);
+    uint64_t *b = reinterpret_cast<uint64_t *>(blob.data() + nd);
+    for (size_t i = 0; i < v.size(); i++) b[i] = v[i].tile_begin;
+    int32_t rc = table_upload(t, blob.data(), blob.size(), s);
+    if (rc != PSX_OK) return rc;
+    *items = static_cast<const D *>(t.dev);
+    *begins = reinterpret_cast<const uint64_t *>(static_cast<const unsigned char *>(t.dev) + nd);
+    return PSX_OK;
+}
+
 struct TimedSpan {
     hipEvent_t a = nullptr, b = nullptr;
     bool valid = false;
@@ -98,6 +114,7 @@ struct psx_ctx {
     uint64_t adam_elems = 0, spill_elems = 0, h2d_bytes = 0, d2h_bytes = 0;
     std::vector<AdamRun> runs;         // scratch for table building
     std::vector<CopySeg> segs;
+    std::vector<unsigned char> blob;   // scratch: descriptors + first tiles, as uploaded
     // host-core execution (PSX_EXEC_CPU), allocated on first use
     CpuPool *pool = nullptr;
     hipStream_t aux = nullptr;         // H2D of the fp16 parameter tiles
@@ -196,11 +213,11 @@ extern "C" int32_t psx_ctx_create(const psx_ctx_config *cfg, psx_ctx **out) {
 #undef PSX_TRY
     int32_t rc;
     const size_t tiles_guess = cfg->staging_tile_elems ? 64 : 0;
-    if ((rc = table_reserve(c->adam_tbl, (3 * cfg->max_chunks + tiles_guess) * sizeof(AdamRun))) != PSX_OK) return bail(rc);
-    if ((rc = table_reserve(c->check_tbl, cfg->max_chunks * sizeof(AdamRun))) != PSX_OK) return bail(rc);
+    if ((rc = table_reserve(c->adam_tbl, (3 * cfg->max_chunks + tiles_guess) * (sizeof(AdamRun) + 8))) != PSX_OK) return bail(rc);
+    if ((rc = table_reserve(c->check_tbl, cfg->max_chunks * (sizeof(AdamRun) + 8))) != PSX_OK) return bail(rc);
     const size_t segs = (size_t)cfg->max_tensors + (size_t)cfg->max_chunks + 1;
-    if ((rc = table_reserve(c->pack_tbl, segs * sizeof(CopySeg))) != PSX_OK) return bail(rc);
-    if ((rc = table_reserve(c->unpack_tbl, segs * sizeof(CopySeg))) != PSX_OK) return bail(rc);
+    if ((rc = table_reserve(c->pack_tbl, segs * (sizeof(CopySeg) + 8))) != PSX_OK) return bail(rc);
+    if ((rc = table_reserve(c->unpack_tbl, segs * (sizeof(CopySeg) + 8))) != PSX_OK) return bail(rc);
     *out = c;
     return PSX_OK;
 }
@@ -465,10 +482,12 @@ int32_t run_copy(psx_ctx *c, Table &tbl, uint32_t dtype, uint64_t tiles, bool ch
     if (rc != PSX_OK) return rc;
     if (tiles == 0) return PSX_OK;
     if (c->segs.size() > 0xFFFFFFFFull) return fail(PSX_ECAP, "too many copy segments");
-    rc = table_upload(tbl, c->segs.data(), c->segs.size() * sizeof(CopySeg), s);
+    const CopySeg *segs_dev = nullptr;
+    const uint64_t *begins_dev = nullptr;
+    rc = upload_described(tbl, c->segs, c->blob, s, &segs_dev, &begins_dev);
     if (rc != PSX_OK) return rc;
     if ((rc = span_begin(c, c->t_pack, s)) != PSX_OK) return rc;
-    PSX_HIP(launch_copy(static_cast<const CopySeg *>(tbl.dev), (uint32_t)c->segs.size(), tiles,
+    PSX_HIP(launch_copy(SegView{segs_dev, begins_dev, (uint32_t)c->segs.size()}, tiles,
                         dtype == PSX_F16 ? 2u : 4u, check ? c->flags_dev : nullptr,
                         check ? c->flags_dev + 1 : nullptr, c->tune, c->n_cu, s));
     return span_end(c, c->t_pack, s);
@@ -542,11 +561,13 @@ extern "C" int32_t psx_overflow_check(psx_ctx *c, const void *const *g16_chunks,
     int32_t rc = set_device_guard(c);
     if (rc != PSX_OK) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    rc = table_upload(c->check_tbl, c->runs.data(), c->runs.size() * sizeof(AdamRun), s);
+    const AdamRun *runs_dev = nullptr;
+    const uint64_t *begins_dev = nullptr;
+    rc = upload_described(c->check_tbl, c->runs, c->blob, s, &runs_dev, &begins_dev);
     if (rc != PSX_OK) return rc;
     PSX_HIP(launch_fill_u32(c->flags_dev, c->flags_n, 0u, s));
     if ((rc = span_begin(c, c->t_check, s)) != PSX_OK) return rc;
-    PSX_HIP(launch_check(static_cast<const AdamRun *>(c->check_tbl.dev), (uint32_t)c->runs.size(), tiles,
+    PSX_HIP(launch_check(RunView{runs_dev, begins_dev, (uint32_t)c->runs.size()}, tiles,
                          c->flags_dev, c->flags_dev + 1, c->tune, c->n_cu, s));
     if ((rc = span_end(c, c->t_check, s)) != PSX_OK) return rc;
     if (per_chunk != nullptr || flag_out != nullptr) return psx_overflow_read(c, per_chunk, n_chunks, flag_out, stream);
@@ -795,15 +816,17 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
         n_direct_recast = c->runs.size() - direct_off - n_direct;
     }
     if (c->runs.size() > 0xFFFFFFFFull) return fail(PSX_ECAP, "psx_chunk_adam_step: too many runs");
-    if ((rc = table_upload(c->adam_tbl, c->runs.data(), c->runs.size() * sizeof(AdamRun), s)) != PSX_OK) return rc;
-    const AdamRun *tbl = static_cast<const AdamRun *>(c->adam_tbl.dev);
+    const AdamRun *tbl = nullptr;
+    const uint64_t *tbl_begins = nullptr;
+    if ((rc = upload_described(c->adam_tbl, c->runs, c->blob, s, &tbl, &tbl_begins)) != PSX_OK) return rc;
+    auto view = [&](size_t off, size_t n) { return RunView{tbl + off, tbl_begins + off, (uint32_t)n}; };
     const uint32_t *flag = use_flag ? c->flags_dev : nullptr;
 
     // ---- overflow check over every gradient chunk
     if (check_first) {
         PSX_HIP(launch_fill_u32(c->flags_dev, c->flags_n, 0u, s));
         if ((rc = span_begin(c, c->t_check, s)) != PSX_OK) return rc;
-        PSX_HIP(launch_check(tbl + n_res + n_recast, (uint32_t)n_check, check_tiles, c->flags_dev, c->flags_dev + 1, c->tune, c->n_cu, s));
+        PSX_HIP(launch_check(view(n_res + n_recast, n_check), check_tiles, c->flags_dev, c->flags_dev + 1, c->tune, c->n_cu, s));
         if ((rc = span_end(c, c->t_check, s)) != PSX_OK) return rc;
     }
 
@@ -830,10 +853,10 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
     c->t_adam.valid = false;
     if (res_tiles != 0) {
         if ((rc = span_begin(c, c->t_adam, s)) != PSX_OK) return rc;
-        PSX_HIP(launch_adam(tbl, (uint32_t)n_res, res_tiles, sc, flag, c->tune, c->n_cu, s));
+        PSX_HIP(launch_adam(view(0, n_res), res_tiles, sc, flag, c->tune, c->n_cu, s));
         if ((rc = span_end(c, c->t_adam, s)) != PSX_OK) return rc;
         if (n_recast != 0)
-            PSX_HIP(launch_recast_if_flag(tbl + n_res, (uint32_t)n_recast, recast_tiles, flag, c->tune, c->n_cu, s));
+            PSX_HIP(launch_recast_if_flag(view(n_res, n_recast), recast_tiles, flag, c->tune, c->n_cu, s));
     }
 
     // ---- host-resident chunks, direct mode: one persistent launch on the side stream, concurrent with
@@ -841,9 +864,9 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
     c->spill_elems = spill_elems; c->h2d_bytes = h2d_bytes; c->d2h_bytes = d2h_bytes;
     bool any_h2d = false, any_d2h = false;
     if (n_direct != 0) {
-        PSX_HIP(launch_adam(tbl + direct_off, (uint32_t)n_direct, direct_tiles, sc, flag, td, c->n_cu, c->h2d));
+        PSX_HIP(launch_adam(view(direct_off, n_direct), direct_tiles, sc, flag, td, c->n_cu, c->h2d));
         if (n_direct_recast != 0)
-            PSX_HIP(launch_recast_if_flag(tbl + direct_off + n_direct, (uint32_t)n_direct_recast, direct_recast_tiles, flag, td, c->n_cu, c->h2d));
+            PSX_HIP(launch_recast_if_flag(view(direct_off + n_direct, n_direct_recast), direct_recast_tiles, flag, td, c->n_cu, c->h2d));
         any_h2d = true;
     }
 
@@ -862,9 +885,9 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
             any_h2d = true;
         }
         Tuning tn = c->tune;
-        PSX_HIP(launch_adam(tbl + t.run, 1u, (t.n + adam_tile - 1) / adam_tile, sc, flag, tn, c->n_cu, s));
+        PSX_HIP(launch_adam(view(t.run, 1), (t.n + adam_tile - 1) / adam_tile, sc, flag, tn, c->n_cu, s));
         if (use_flag && t.alias)
-            PSX_HIP(launch_recast_if_flag(tbl + t.run, 1u, (t.n + recast_tile - 1) / recast_tile, flag, tn, c->n_cu, s));
+            PSX_HIP(launch_recast_if_flag(view(t.run, 1), (t.n + recast_tile - 1) / recast_tile, flag, tn, c->n_cu, s));
         if (t.dst[0] != nullptr) {
             PSX_HIP(hipEventRecord(c->ev_k[e], s));
             PSX_HIP(hipStreamWaitEvent(c->d2h, c->ev_k[e], 0));
