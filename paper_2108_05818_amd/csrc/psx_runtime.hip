@@ -1,6 +1,8 @@
 // Host runtime behind the C ABI: context, descriptor tables, the multi-tensor
-// pack/unpack and overflow-check calls, and the Adam step with its
-// double-buffered H2D / update / D2H pipeline for host-resident chunks.
+// pack/unpack and overflow-check calls, and the Adam step: one launch over the
+// HBM-resident chunks and, for host-resident chunks, a launch that works on the
+// pinned buffers over the link, a staged H2D / update / D2H pipeline, or the
+// host cores (fp16 tiles copied out and in around an in-place host update).
 #include <chrono>
 #include <cmath>
 #include <cstring>
@@ -698,6 +700,23 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
             const bool staged = ch.exec != PSX_EXEC_CPU &&
                                 !(c->tune.host_mode == 1 && ch.loc_in == PSX_LOC_HOST && ch.loc_out == PSX_LOC_HOST);
             if (staged && T == 0) return fail(PSX_ENOSTAGING, "psx_chunk_adam_step: chunk %zu is host-resident but the context has no staging", k);
+            if (!staged && ch.exec != PSX_EXEC_CPU) {
+                // the kernel will dereference these host pointers: they must be page-locked memory the
+                // device can reach, over their whole used range, or the launch would fault the GPU
+                const void *hp[3] = {ch.p32_host, ch.m_host, ch.v_host};
+                for (int j = 0; j < 3; j++) {
+                    const char *ends[2] = {static_cast<const char *>(hp[j]), static_cast<const char *>(hp[j]) + (ch.used * sizeof(float) - 1)};
+                    for (const char *q : ends) {
+                        hipPointerAttribute_t at;
+                        const hipError_t e = hipPointerGetAttributes(&at, q);
+                        if (e != hipSuccess || at.type != hipMemoryTypeHost) {
+                            (void)hipGetLastError();
+                            return fail(PSX_EINVAL, "psx_chunk_adam_step: chunk %zu: host state %d is not pinned, device-accessible memory "
+                                                    "(allocate it with hipHostMalloc / psx_pinned_alloc, or select PSX_TUNE_HOST_MODE 0)", k, j);
+                        }
+                    }
+                }
+            }
         }
     }
     if ((rc = set_device_guard(c)) != PSX_OK) return rc;

@@ -375,6 +375,11 @@ def test_bad_arguments_touch_nothing():
         with pytest.raises(psx.PsxError) as e:
             psx.psx_chunk_adam_step(ctx, psx.make_chunks(cl.specs(loc=[(H, G)], host=[hs])), psx.make_hyper())
         assert e.value.code == psx.PSX_ENOSTAGING
+        # direct access to host states that are not page-locked would fault the GPU: refused up front
+        pageable = [torch.zeros(64) for _ in range(3)]
+        with pytest.raises(psx.PsxError) as e:
+            psx.psx_chunk_adam_step(ctx, psx.make_chunks(cl.specs(loc=[(H, H)], host=[pageable])), psx.make_hyper())
+        assert e.value.code == psx.PSX_EINVAL and "not pinned" in str(e.value)
         with pytest.raises(psx.PsxError) as e:      # misaligned chunk base
             bad = cl.specs()
             bad[0]["p32"] = cl.p32[0].data_ptr() + 4
