@@ -14,6 +14,7 @@ Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
   python bench.py [--gpus 1] [--steps 20] [--warmup 3] [--workload gpt1b|tiny|gpt12b|ragged]
 """
 import argparse
+import ctypes
 import json
 import os
 import sys
@@ -128,6 +129,9 @@ def setup(w, dev, host_fraction=0.0, staging_tile_elems=4 << 20, staging_slots=3
     st.o_ptrs = psx.ptr_array(st.out_t)
     st.scaler = psx.make_scaler(w.loss_scale, w.growth_interval)
     st.numel_arr = list(w.numel)
+    st.numel_c = (ctypes.c_uint64 * max(len(w.numel), 1))(*w.numel)
+    st.slots_c = (psx.psx_slot * max(len(w.numel), 1))()
+    st.used_c = (ctypes.c_uint64 * st.nch)()
     return st
 
 
@@ -135,7 +139,14 @@ def run_step(st, fused_check=False):
     """One pass of the hot path; returns the overflow flag."""
     from paper_2108_05818_amd import psx
     w, ctx, C = st.w, st.ctx, st.C
-    slots, used = psx.psx_chunk_layout(st.numel_arr, C)                       # a1
+    # a1: the layout call itself, into arrays marshalled once (building ctypes arrays of thousands of
+    # tensor sizes every step is Python overhead, not the call)
+    nch_out = ctypes.c_size_t(0)
+    rc = psx.lib().psx_chunk_layout(st.numel_c, len(st.numel_arr), C, 0, st.slots_c, st.used_c, st.nch,
+                                    ctypes.byref(nch_out))
+    if rc != 0 or nch_out.value != st.nch:
+        raise RuntimeError(f"psx_chunk_layout: {rc} {psx.psx_last_error()}")
+    slots = st.slots_c
     n = len(st.numel_arr)
     if fused_check:
         psx.psx_overflow_reset(ctx)

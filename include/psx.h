@@ -113,7 +113,9 @@ int32_t psx_ctx_destroy(psx_ctx *ctx);
  * dtype         PSX_F16 (2-byte elements) or PSX_F32 (4-byte elements)
  * tensors[n]    host array of device pointers, tensor i has slots[i].numel elements
  * slots[n]      host, from psx_chunk_layout
- * chunks[]      host array of n_chunks device pointers, each chunk_elems elements
+ * chunks[]      host array of n_chunks device pointers, each chunk_elems elements (page-locked,
+ *               device-accessible host memory works as well, at host-link speed: that is how the
+ *               fp32 params of host-resident chunks are packed)
  * flags         PSX_PACK_CHECK_OVERFLOW (psx_pack, PSX_F16 only): while copying,
  *               OR the inf/nan test of every copied element into the context's
  *               overflow flags (see psx_overflow_check; clear them first with
