@@ -58,7 +58,8 @@ class State:
 def setup(w, dev, host_fraction=0.0, staging_tile_elems=4 << 20, staging_slots=3, keep_params="all", cpu_share=0.0):
     """Allocate chunk lists and seeded inputs on the device (and pinned host memory for
     host-resident chunks); pack the fp32 params tensor by tensor; m = v = 0.
-    keep_params: "all" keeps every fp32 source tensor, an int keeps only the first that many.
+    keep_params: "all" keeps every fp32 source tensor, an int keeps only the first that many, a set keeps
+    those indices.
     cpu_share: share of the host-resident chunks that the host cores update (PSX_EXEC_CPU); the rest of
     them is updated by the GPU over the link."""
     import torch
@@ -110,7 +111,8 @@ def setup(w, dev, host_fraction=0.0, staging_tile_elems=4 << 20, staging_slots=3
         lib_chunks = p32_dst
         psx.lib().psx_pack(st.ctx, psx.PSX_F32, psx.ptr_array([t]), one, 1, lib_chunks, st.nch, C, 0,
                            torch.cuda.current_stream().cuda_stream)
-        st.p_t.append(t if keep_params == "all" or i < keep_params else None)
+        keep = keep_params == "all" or (i in keep_params if isinstance(keep_params, (set, frozenset)) else i < keep_params)
+        st.p_t.append(t if keep else None)
     torch.cuda.synchronize()
     st.g_t = [W.grads_f16_torch(s, w.seed + 100000 + i, w.loss_scale, dev) for i, s in enumerate(w.numel)]
     st.out_t = [torch.empty(s, dtype=torch.float16, device=dev) for s in w.numel]

@@ -19,6 +19,17 @@ from gpu_util import DEV, bits16, f32, from_bits16
 pytestmark = pytest.mark.gpu
 
 
+@pytest.fixture(autouse=True)
+def _release_cached_device_memory():
+    """These tests allocate tens to hundreds of GB; start each from an empty allocator cache."""
+    import gc
+    gc.collect()
+    torch.cuda.empty_cache()
+    yield
+    gc.collect()
+    torch.cuda.empty_cache()
+
+
 class Sample:
     """Oracle-side mirror of a subset of chunks of a bench.State, built only from the seeded tensors."""
 
@@ -431,3 +442,43 @@ def test_empty_calls_do_nothing():
         assert r.h2d_alone > 1.0 and r.d2h_alone > 1.0 and r.each_way_both > 0.5
     finally:
         psx.psx_ctx_destroy(ctx)
+
+
+def test_config4_gpt12b_full_size_sampled_chunks(orc):
+    """GPT-12.6B at full size (12.85 G elements, 244 chunks of 64 Mi), the last 98 chunks host-resident and
+    updated over the link, exactly as `bench.py --workload gpt12b` runs it; oracle on four whole chunks."""
+    import psutil
+    if psutil.virtual_memory().available < 120 * (1 << 30) or torch.cuda.mem_get_info()[0] < 250 * (1 << 30):
+        pytest.skip("needs 120 GiB of host memory and 250 GiB of HBM")
+    w = W.config4_gpt12b()
+    C = w.chunk_elems
+    o_slots, o_used = orc.chunk_layout(w.numel, C)
+    nch = len(o_used)
+    first_host = nch - round(0.4 * nch)
+    ks = [3, first_host - 1, first_host, nch - 1]
+    needed = {i for i, s in enumerate(w.numel) if s and any(
+        o_slots[i].chunk * C + o_slots[i].offset < (k + 1) * C and o_slots[i].chunk * C + o_slots[i].offset + s > k * C
+        for k in ks)}
+    st = bench.setup(w, DEV, host_fraction=0.4, keep_params=needed)
+    try:
+        assert st.nch == 244 and st.n_host == 98 and w.n_elems == 12848143360
+        sm = Sample(orc, st, ks)
+        assert set(sm.idx) == needed
+        sm.pack(st.p_t, sm.p32)
+        where = [None if st.host[k] is None else st.host[k] for k in range(st.nch)]
+        compare_sample_states(sm, st, where, "after param pack")
+        for step in range(2):
+            flag = bench.run_step(st, fused_check=True)
+            torch.cuda.synchronize()
+            sm.pack(st.g_t, sm.g16, as_bits16=True)
+            assert flag == sm.flag() == 0
+            sm.adam(orc.hyper(lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps, weight_decay=w.weight_decay,
+                              adamw_mode=w.adamw_mode, step=step + 1, loss_scale=w.loss_scale))
+            compare_sample_states(sm, st, where, f"step {step}")
+        tm = psx.psx_ctx_get_timing(st.ctx)
+        assert tm.spill_elems == sum(st.used[first_host:]) == 5139102720
+    finally:
+        psx.psx_ctx_destroy(st.ctx)
+        for hs in st.host:
+            for b in hs or []:
+                b.free()
