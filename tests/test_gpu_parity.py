@@ -469,3 +469,47 @@ def test_host_chunks_updated_by_the_host_cores(orc, alias, wd, adamw, isa):
         for hs in host:
             for b in hs or []:
                 b.free()
+
+
+def test_step_on_a_side_stream_orders_itself_with_that_stream(orc):
+    """Everything a call starts on the context's own streams is joined back into the caller's stream:
+    synchronising that stream alone (not the device) must show the finished step, host chunks included."""
+    ctx = psx.psx_ctx_create(max_chunks=16, max_tensors=4, staging_tile_elems=4096, staging_slots=2)
+    side = torch.cuda.Stream()
+    host = []
+    try:
+        used = [20000, 12289, 4097, 9000, 16000]
+        loc = [(G, G), (H, H), (H, H), (G, H), (H, G)]
+        ex = [0, 0, 1, 0, 0]
+        Cn = 20000
+        cl = ChunkLists(used, Cn)
+        fill_state(cl, 9900, 1024.0, zero_mv=False)
+        for k in range(cl.n):
+            hs = [psx.PinnedF32(Cn, fill=0.0) for _ in range(3)]
+            if loc[k][0] == H:
+                for hbuf, name in zip(hs, ("p32", "m", "v")):
+                    hbuf.np[...] = cl.np[name][k]
+                    getattr(cl, name)[k].view(torch.int32).fill_(0x0BADBEEF)
+            host.append(hs)
+        torch.cuda.synchronize()
+        specs = cl.specs(loc=loc, host=host)
+        for s, e in zip(specs, ex):
+            s["exec"] = e
+        hp = dict(lr=1e-3, weight_decay=0.01, step=4, loss_scale=1024.0)
+        with torch.cuda.stream(side):
+            psx.psx_chunk_adam_step(ctx, psx.make_chunks(specs), psx.make_hyper(**hp), psx.PSX_STEP_CHECK_FIRST)
+            out = [cl.p16[k].clone() for k in range(cl.n)]            # queued on the same stream, after the step
+        side.synchronize()
+        assert cl.oracle_step(orc, orc.hyper(**hp)) == 0
+        for k in range(cl.n):
+            u = used[k]
+            assert np.array_equal(bits16(out[k])[:u], cl.np["p16"][k][:u])
+            for j, name in enumerate(("p32", "m", "v")):
+                got = host[k][j].np if loc[k][1] == H else f32(getattr(cl, name)[k])
+                assert got[:u].tobytes() == cl.np[name][k][:u].tobytes(), (k, name)
+    finally:
+        torch.cuda.synchronize()
+        psx.psx_ctx_destroy(ctx)
+        for hs in host:
+            for b in hs:
+                b.free()
