@@ -513,3 +513,50 @@ def test_step_on_a_side_stream_orders_itself_with_that_stream(orc):
         for hs in host:
             for b in hs:
                 b.free()
+
+
+@pytest.mark.parametrize("exec_cpu", [0, 1])
+def test_fp32_denormals_are_kept(orc, exec_cpu):
+    """A huge loss scale with tiny gradients drives g, m, v and the products on the way through the fp32
+    denormal range; the GPU kernel and the host-core kernel must keep denormals exactly as the oracle does."""
+    ctx = psx.psx_ctx_create(max_chunks=4, max_tensors=4)
+    host = None
+    try:
+        n = 70000
+        rng = np.random.default_rng(123)
+        g = rng.integers(0, 0x0C00, size=n).astype(np.uint16)            # fp16 subnormals and the smallest normals
+        g |= (rng.integers(0, 2, size=n).astype(np.uint16) << 15)
+        cl = ChunkLists([n], n + 3)
+        cl.set("g16", 0, g)
+        cl.set("p32", 0, W.params_np(n, 77) * np.float32(1e-30))         # params near the denormal range too
+        tiny = (rng.random(n, dtype=np.float32) * np.float32(1e-38)).astype(np.float32)
+        cl.set("m", 0, tiny * np.float32(0.3) * np.where(rng.random(n) < 0.5, -1, 1).astype(np.float32))
+        cl.set("v", 0, tiny)
+        assert np.any((np.abs(cl.np["v"][0][:n]) < 1.1754944e-38) & (cl.np["v"][0][:n] != 0))
+        loc, hostbufs = None, None
+        if exec_cpu:
+            host = [psx.PinnedF32(n) for _ in range(3)]
+            for hbuf, name in zip(host, ("p32", "m", "v")):
+                hbuf.np[...] = cl.np[name][0][:n]
+            loc, hostbufs = [(H, H)], [host]
+        specs = cl.specs(loc=loc, host=hostbufs)
+        specs[0]["exec"] = exec_cpu
+
+        class HostView:
+            def __init__(self, b): self.b = b
+            def cpu(self): return self
+            def numpy(self): return np.concatenate([self.b.np, cl.np["p32"][0][n:]])     # padding as in the mirror
+        where = [[HostView(b) for b in host]] if exec_cpu else None
+        for t, scale in ((1, 2.0 ** 40), (2, 2.0 ** 36), (3, 2.0 ** 44)):
+            hp = dict(lr=1e-3, eps=1e-30, weight_decay=0.0, step=t, loss_scale=scale)
+            psx.psx_chunk_adam_step(ctx, psx.make_chunks(specs), psx.make_hyper(**hp), psx.PSX_STEP_CHECK_FIRST)
+            torch.cuda.synchronize()
+            assert cl.oracle_step(orc, orc.hyper(**hp)) == 0
+            assert cl.compare(f"t={t}", where=where) == 0.0
+            v_now = cl.np["v"][0][:n]
+            if t == 1:                                              # denormals really occur
+                assert np.count_nonzero((v_now != 0) & (np.abs(v_now) < 1.1754944e-38)) > 100
+    finally:
+        psx.psx_ctx_destroy(ctx)
+        for b in host or []:
+            b.free()
