@@ -260,7 +260,8 @@ int32_t psx_loss_scale_update(psx_scaler *s, uint32_t overflow);
  *   PSX_TUNE_COPY_BLOCKS_PER_CU  same as the first, for pack/unpack/check
  *   PSX_TUNE_ADAM_THREADS        threads per workgroup of the Adam kernel: 64 or 256
  *   PSX_TUNE_ADAM_WG_PER_CU      cap on Adam workgroups resident per CU (0 = none)
- *   PSX_TUNE_COPY_UNROLL         16-byte vectors per thread and tile of pack/unpack: 1 or 4
+ *   PSX_TUNE_COPY_UNROLL         16-byte vectors per thread and tile of pack/unpack: 1 or 4; 0 = 4 when more
+ *                                than 1024 tensors are passed, else 1 (default)
  *   PSX_TUNE_HOST_MODE           host-resident (HOST -> HOST) chunks: 0 = staged through device tiles with
  *                                H2D / D2H copies on the copy streams; 1 = the kernel reads and writes the
  *                                pinned buffers directly over the host link (they must be device-accessible,

@@ -344,8 +344,9 @@ hipError_t launch_check(const RunView &rv, uint64_t n_tiles, uint32_t *flag,
 // One segment = one contiguous piece of a tensor inside one chunk.  A tile is
 // U x 4 KiB of it.  The destination is brought to 16-byte alignment with a few
 // single-element copies, then written with 16-byte stores; the source is read
-// with 16-byte loads when it happens to share that alignment, else with
-// 4-byte or 2-byte loads (every access is naturally aligned).
+// with 16-byte loads as well: directly when it happens to share that
+// alignment, else as pairs of aligned vectors shifted into place with
+// v_alignbyte (every access is naturally aligned).
 template <int ES>
 struct ElemT;
 template <>
@@ -409,22 +410,35 @@ __global__ __launch_bounds__(kThreads) void copy_kernel(const CopySeg *__restric
                     bad |= test_vec<ES, CHECK>(w);
                     gptr<u32x4>(db)[i] = w;
                 }
-            } else if ((mis & 3u) == 0) {
-                for (uint32_t i = tid; i < nvec; i += kThreads) {
-                    const PSX_GLOBAL uint32_t *q = gptr<uint32_t>(sb) + 4u * i;
-                    u32x4 w;
-                    w[0] = q[0]; w[1] = q[1]; w[2] = q[2]; w[3] = q[3];
-                    bad |= test_vec<ES, CHECK>(w);
-                    gptr<u32x4>(db)[i] = w;
-                }
             } else {
-                // only 2-byte elements can be off by 2 modulo 4
+                // source and destination disagree modulo 16: read the two 16-byte-aligned source vectors
+                // that cover the wanted 16 bytes and shift them into place.  `lo` holds the first wanted
+                // byte and `hi` the last one, so both loads stay inside 16-byte blocks that contain valid
+                // source bytes (never a page the tensor does not touch).
+                const PSX_GLOBAL u32x4 *ab = gptr<u32x4>(sb - mis);
+                const uint32_t q = mis >> 2, b = mis & 3u;      // whole words and bytes to drop (uniform per tile)
                 for (uint32_t i = tid; i < nvec; i += kThreads) {
-                    const PSX_GLOBAL uint16_t *q = gptr<uint16_t>(sb) + 8u * i;
+                    const u32x4 lo = ab[i], hi = ab[i + 1];
+                    uint32_t d[9] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3], 0u};
                     u32x4 w;
+                    switch (q) {
+                        case 0:
 #pragma unroll
-                    for (int k = 0; k < 4; k++)
-                        w[k] = (uint32_t)q[2 * k] | ((uint32_t)q[2 * k + 1] << 16);
+                            for (int k = 0; k < 4; k++) w[k] = __builtin_amdgcn_alignbyte(d[k + 1], d[k], b);
+                            break;
+                        case 1:
+#pragma unroll
+                            for (int k = 0; k < 4; k++) w[k] = __builtin_amdgcn_alignbyte(d[k + 2], d[k + 1], b);
+                            break;
+                        case 2:
+#pragma unroll
+                            for (int k = 0; k < 4; k++) w[k] = __builtin_amdgcn_alignbyte(d[k + 3], d[k + 2], b);
+                            break;
+                        default:
+#pragma unroll
+                            for (int k = 0; k < 4; k++) w[k] = __builtin_amdgcn_alignbyte(d[k + 4], d[k + 3], b);
+                            break;
+                    }
                     bad |= test_vec<ES, CHECK>(w);
                     gptr<u32x4>(db)[i] = w;
                 }

@@ -117,6 +117,7 @@ struct psx_ctx {
     std::vector<AdamRun> runs;         // scratch for table building
     std::vector<CopySeg> segs;
     std::vector<unsigned char> blob;   // scratch: descriptors + first tiles, as uploaded
+    int copy_unroll_now = 1;           // tile shape the segments in `segs` were cut for
     // host-core execution (PSX_EXEC_CPU), allocated on first use
     CpuPool *pool = nullptr;
     hipStream_t aux = nullptr;         // H2D of the fp16 parameter tiles
@@ -282,7 +283,7 @@ extern "C" int32_t psx_ctx_set_tuning(psx_ctx *c, uint32_t key, int64_t value) {
             c->tune.copy_blocks_per_cu = (int)value;
             break;
         case PSX_TUNE_COPY_UNROLL:
-            if (value != 1 && value != 4) return fail(PSX_EINVAL, "copy unroll must be 1 or 4");
+            if (value != 0 && value != 1 && value != 4) return fail(PSX_EINVAL, "copy unroll must be 0 (by tensor count), 1 or 4");
             c->tune.copy_unroll = (int)value;
             break;
         case PSX_TUNE_HOST_MODE:
@@ -439,7 +440,8 @@ int32_t build_segments(psx_ctx *c, const char *who, uint32_t dtype, const void *
     if (n_chunks > c->cfg.max_chunks) return fail(PSX_ECAP, "%s: %zu chunks, context holds %llu", who, n_chunks, (unsigned long long)c->cfg.max_chunks);
     if (n > c->cfg.max_tensors) return fail(PSX_ECAP, "%s: %zu tensors, context holds %llu", who, n, (unsigned long long)c->cfg.max_tensors);
     const uint32_t es = dtype == PSX_F16 ? 2u : 4u;
-    const uint64_t tile_elems = copy_tile_bytes(c->tune) / es;
+    c->copy_unroll_now = copy_unroll_for(c->tune, n);
+    const uint64_t tile_elems = copy_tile_bytes(c->copy_unroll_now) / es;
     const uint64_t total = (uint64_t)n_chunks * chunk_elems;
     for (size_t k = 0; k < n_chunks; k++) {
         if (chunks[k] == nullptr) return fail(PSX_EINVAL, "%s: chunk %zu is NULL", who, k);
@@ -489,9 +491,11 @@ int32_t run_copy(psx_ctx *c, Table &tbl, uint32_t dtype, uint64_t tiles, bool ch
     rc = upload_described(tbl, c->segs, c->blob, s, &segs_dev, &begins_dev);
     if (rc != PSX_OK) return rc;
     if ((rc = span_begin(c, c->t_pack, s)) != PSX_OK) return rc;
+    Tuning tn = c->tune;
+    tn.copy_unroll = c->copy_unroll_now;
     PSX_HIP(launch_copy(SegView{segs_dev, begins_dev, (uint32_t)c->segs.size()}, tiles,
                         dtype == PSX_F16 ? 2u : 4u, check ? c->flags_dev : nullptr,
-                        check ? c->flags_dev + 1 : nullptr, c->tune, c->n_cu, s));
+                        check ? c->flags_dev + 1 : nullptr, tn, c->n_cu, s));
     return span_end(c, c->t_pack, s);
 }
 
