@@ -11,7 +11,7 @@ parameter set, every part of it in the HIP library behind include/psx.h:
   synchronises) and loss-scale update.
 Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps 20] [--warmup 3] [--workload gpt1b|tiny|gpt12b|ragged]
+  python bench.py [--gpus 1] [--steps 20] [--warmup 3] [--workload gpt1b|tiny|gpt12b|ragged|gpt20b]
 """
 import argparse
 import ctypes
@@ -35,7 +35,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="gpt1b", choices=["gpt1b", "tiny", "gpt12b", "ragged"])
+    ap.add_argument("--workload", default="gpt1b", choices=["gpt1b", "tiny", "gpt12b", "ragged", "gpt20b"])
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (shape-preserving scale-down)")
     ap.add_argument("--chunk-elems", type=int, default=0, help="override the chunk size (elements)")
     ap.add_argument("--host-fraction", type=float, default=-1.0, help="share of chunks whose fp32 states live in pinned host memory")
@@ -55,13 +55,17 @@ class State:
     pass
 
 
-def setup(w, dev, host_fraction=0.0, staging_tile_elems=4 << 20, staging_slots=3, keep_params="all", cpu_share=0.0):
+def setup(w, dev, host_fraction=0.0, staging_tile_elems=4 << 20, staging_slots=3, keep_params="all", cpu_share=0.0,
+          plans=None):
     """Allocate chunk lists and seeded inputs on the device (and pinned host memory for
     host-resident chunks); pack the fp32 params tensor by tensor; m = v = 0.
     keep_params: "all" keeps every fp32 source tensor, an int keeps only the first that many, a set keeps
     those indices.
     cpu_share: share of the host-resident chunks that the host cores update (PSX_EXEC_CPU); the rest of
-    them is updated by the GPU over the link."""
+    them is updated by the GPU over the link.
+    plans: optional list of per-step residencies (one PSX_LOC_* per chunk); plans[0] is where the fp32
+    states start.  A chunk gets a device home if any plan keeps it in HBM and a pinned home if any plan
+    puts it on the host.  Without plans the last host_fraction of the chunks live on the host for good."""
     import torch
     from paper_2108_05818_amd import psx
     from paper_2108_05818_amd import workloads as W
@@ -71,14 +75,19 @@ def setup(w, dev, host_fraction=0.0, staging_tile_elems=4 << 20, staging_slots=3
     st.C = w.chunk_elems
     st.slots, st.used = psx.psx_chunk_layout(w.numel, st.C)
     st.nch = len(st.used)
-    n_host = int(round(host_fraction * st.nch))
+    if plans is None:
+        n_host = int(round(host_fraction * st.nch))
+        plans = [[psx.PSX_LOC_HBM] * (st.nch - n_host) + [psx.PSX_LOC_HOST] * n_host]
+    st.loc = list(plans[0])
+    need_dev = [any(pl[k] == psx.PSX_LOC_HBM for pl in plans) for k in range(st.nch)]
+    need_host = [any(pl[k] == psx.PSX_LOC_HOST for pl in plans) for k in range(st.nch)]
+    n_host = sum(need_host)
     st.n_host = n_host
     n_cpu = int(round(cpu_share * n_host))
     st.n_cpu = n_cpu
     st.ctx = psx.psx_ctx_create(max_chunks=st.nch, max_tensors=len(w.numel),
                                 staging_tile_elems=staging_tile_elems if n_host else 0, staging_slots=staging_slots)
     C = st.C
-    first_host = st.nch - n_host
 
     def chunk_list(dtype, n):
         """One chunk list = one arena, chunk k at offset k*C (the paper's ChunkLists: a list of chunks per
@@ -89,21 +98,20 @@ def setup(w, dev, host_fraction=0.0, staging_tile_elems=4 << 20, staging_slots=3
         return [arena[k * C:(k + 1) * C] for k in range(n)]
     st.p16 = chunk_list(torch.float16, st.nch)
     st.g16 = chunk_list(torch.float16, st.nch)
-    # fp32 states: the first chunks in HBM, the last n_host chunks in pinned host memory
-    p_list, m_list, v_list = (chunk_list(torch.float32, first_host) for _ in range(3))
+    # fp32 states: device homes (one arena per list over the chunks that are ever HBM-resident) and
+    # pinned host homes (for the chunks that are ever host-resident)
+    p_list, m_list, v_list = (iter(chunk_list(torch.float32, sum(need_dev))) for _ in range(3))
     st.p32, st.m, st.v, st.host = [], [], [], []
     for k in range(st.nch):
-        if k < first_host:
-            st.p32.append(p_list[k]); st.m.append(m_list[k]); st.v.append(v_list[k])
-            st.host.append(None)
-        else:
-            st.p32.append(None); st.m.append(None); st.v.append(None)
-            # a host-resident chunk needs room for its used prefix only (pinned memory is scarce)
-            st.host.append([psx.PinnedF32(st.used[k]) for _ in range(3)])
+        st.p32.append(next(p_list) if need_dev[k] else None)
+        st.m.append(next(m_list) if need_dev[k] else None)
+        st.v.append(next(v_list) if need_dev[k] else None)
+        # a host-resident chunk needs room for its used prefix only (pinned memory is scarce)
+        st.host.append([psx.PinnedF32(st.used[k]) for _ in range(3)] if need_host[k] else None)
     # seeded tensors (the "model"): fp32 params, packed one tensor at a time straight into the chunk
     # that will hold them (pinned host chunks are device-accessible, so the pack kernel writes them too),
     # and one set of scaled fp16 gradients
-    p32_dst = psx.ptr_array([st.p32[k] if st.host[k] is None else st.host[k][0] for k in range(st.nch)])
+    p32_dst = psx.ptr_array([st.p32[k] if st.loc[k] == psx.PSX_LOC_HBM else st.host[k][0] for k in range(st.nch)])
     st.p_t = []
     for i, s in enumerate(w.numel):
         t = W.params_torch(s, w.seed + i, dev)
@@ -116,17 +124,16 @@ def setup(w, dev, host_fraction=0.0, staging_tile_elems=4 << 20, staging_slots=3
     torch.cuda.synchronize()
     st.g_t = [W.grads_f16_torch(s, w.seed + 100000 + i, w.loss_scale, dev) for i, s in enumerate(w.numel)]
     st.out_t = [torch.empty(s, dtype=torch.float16, device=dev) for s in w.numel]
-    specs = []
+    st.specs = []
     for k in range(st.nch):
-        s = dict(g16=st.g16[k], p16=st.p16[k], used=st.used[k])
-        if st.host[k] is None:
-            s.update(p32=st.p32[k], m=st.m[k], v=st.v[k], loc_in=psx.PSX_LOC_HBM, loc_out=psx.PSX_LOC_HBM)
-        else:
+        s = dict(g16=st.g16[k], p16=st.p16[k], used=st.used[k], loc_in=st.loc[k], loc_out=st.loc[k])
+        if need_dev[k]:
+            s.update(p32=st.p32[k], m=st.m[k], v=st.v[k])
+        if need_host[k]:
             s.update(p32_host=st.host[k][0], m_host=st.host[k][1], v_host=st.host[k][2],
-                     loc_in=psx.PSX_LOC_HOST, loc_out=psx.PSX_LOC_HOST,
                      exec=psx.PSX_EXEC_CPU if k >= st.nch - n_cpu else psx.PSX_EXEC_GPU)
-        specs.append(s)
-    st.chunks = psx.make_chunks(specs)
+        st.specs.append(s)
+    st.chunks = psx.make_chunks(st.specs)
     st.t_ptrs = psx.ptr_array(st.g_t)
     st.o_ptrs = psx.ptr_array(st.out_t)
     st.scaler = psx.make_scaler(w.loss_scale, w.growth_interval)
@@ -137,10 +144,21 @@ def setup(w, dev, host_fraction=0.0, staging_tile_elems=4 << 20, staging_slots=3
     return st
 
 
-def run_step(st, fused_check=False):
-    """One pass of the hot path; returns the overflow flag."""
+def run_step(st, fused_check=False, new_loc=None):
+    """One pass of the hot path; returns the overflow flag.  new_loc: where each chunk's fp32 states are
+    to live after this step (default: where they are)."""
     from paper_2108_05818_amd import psx
     w, ctx, C = st.w, st.ctx, st.C
+    if new_loc is not None and list(new_loc) != st.loc:
+        for k, s in enumerate(st.specs):
+            s["loc_in"], s["loc_out"] = st.loc[k], new_loc[k]
+        st.chunks = psx.make_chunks(st.specs)
+        st.loc, st.settled = list(new_loc), False
+    elif not getattr(st, "settled", True):          # the chunks that moved last step now stay where they are
+        for k, s in enumerate(st.specs):
+            s["loc_in"] = s["loc_out"] = st.loc[k]
+        st.chunks = psx.make_chunks(st.specs)
+        st.settled = True
     # a1: the layout call itself, into arrays marshalled once (building ctypes arrays of thousands of
     # tensor sizes every step is Python overhead, not the call)
     nch_out = ctypes.c_size_t(0)
@@ -250,15 +268,28 @@ def main():
         w = W.config3_ragged()
     elif a.workload == "gpt12b":
         w = W.config4_gpt12b(a.layers or 40)
+    elif a.workload == "gpt20b":
+        # 44 layers need 170 GB of pinned memory; 12 layers of the same tensors fit this box's limit
+        w = W.config5_gpt20b(a.layers or 12)
     else:
         w = W.config2_gpt1b(a.layers or 20)
     if a.chunk_elems:
         w.chunk_elems = a.chunk_elems
         w.name += f"-C{a.chunk_elems}"
     host_fraction = w.host_fraction if a.host_fraction < 0 else a.host_fraction
+    plans = None
+    if a.workload == "gpt20b":
+        # the HBM budget for fp32 states moves by +-30 % from step to step (seeded); the planner keeps the
+        # fullest chunks that fit, the rest live in pinned host memory; chunks at the margin change residence
+        # while they are updated
+        _, used = psx.psx_chunk_layout(w.numel, w.chunk_elems)
+        per_chunk = 12 * w.chunk_elems
+        budget = lambda t: int(round(len(used) * W.budget_fraction(t, 1.0 - host_fraction, w.budget_jitter, w.seed))) * per_chunk
+        plans = [psx.psx_plan_residency(used, w.chunk_elems, budget(t))[0] for t in range(a.warmup + a.steps + 1)]
     # the fp32 source tensors are needed again only by the oracle leg, and only the first few of them
     st = setup(w, dev, host_fraction, a.staging_tile, a.staging_slots,
-               keep_params=0 if a.no_cpu_baseline else CPU_BASELINE_TENSORS, cpu_share=a.cpu_share)
+               keep_params=0 if a.no_cpu_baseline else CPU_BASELINE_TENSORS,
+               cpu_share=0.0 if plans else a.cpu_share, plans=plans)
     tune_keys = {"bpc": psx.PSX_TUNE_ADAM_BLOCKS_PER_CU, "unroll": psx.PSX_TUNE_ADAM_UNROLL,
                  "nt": psx.PSX_TUNE_NONTEMPORAL, "cbpc": psx.PSX_TUNE_COPY_BLOCKS_PER_CU,
                  "threads": psx.PSX_TUNE_ADAM_THREADS, "wg": psx.PSX_TUNE_ADAM_WG_PER_CU,
@@ -282,17 +313,28 @@ def main():
         cpu = cpu_baseline(st)
 
     psx.psx_ctx_set_profiling(st.ctx, 1)
-    for _ in range(a.warmup):
-        run_step(st, not a.separate_check)
+    plan_at = (lambda t: plans[t]) if plans else (lambda t: None)
+    for i in range(a.warmup):
+        run_step(st, not a.separate_check, plan_at(1 + i))
     torch.cuda.synchronize()
     phase = {"pack_ms": 0.0, "check_ms": 0.0, "adam_ms": 0.0, "spill_ms": 0.0}
+    link = {"h2d": 0, "d2h": 0, "min_h2d": 0, "min_d2h": 0, "moved_chunks": 0, "resident_chunks": []}
     t0 = time.perf_counter()
     skipped = 0
-    for _ in range(a.steps):
-        skipped += run_step(st, not a.separate_check)
+    for i in range(a.steps):
+        before = list(st.loc)
+        skipped += run_step(st, not a.separate_check, plan_at(1 + a.warmup + i))
         tm = psx.psx_ctx_get_timing(st.ctx)      # events of this step; the stream is already drained
         phase["pack_ms"] += tm.pack_ms; phase["check_ms"] += tm.check_ms
         phase["adam_ms"] += tm.adam_ms; phase["spill_ms"] += tm.spill_ms
+        if plans:
+            # every chunk that starts the step on the host must come in once, every chunk that ends it there
+            # must go out once: 12 bytes per used element each
+            link["h2d"] += int(tm.h2d_bytes); link["d2h"] += int(tm.d2h_bytes)
+            link["min_h2d"] += 12 * sum(u for u, l in zip(st.used, before) if l == psx.PSX_LOC_HOST)
+            link["min_d2h"] += 12 * sum(u for u, l in zip(st.used, st.loc) if l == psx.PSX_LOC_HOST)
+            link["moved_chunks"] += sum(x != y for x, y in zip(before, st.loc))
+            link["resident_chunks"].append(sum(l == psx.PSX_LOC_HBM for l in st.loc))
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms = dt * 1e3 / a.steps
@@ -341,6 +383,12 @@ def main():
                             "host_part_gelem_s": (tm.spill_elems + tm.cpu_elems) / link_s / 1e9 if link_s else None,
                             "spill_elems": int(tm.spill_elems), "spill_ms": phase["spill_ms"],
                             "spill_gelem_s": tm.spill_elems / link_s / 1e9 if link_s else None}
+    if plans:
+        moved = link["h2d"] + link["d2h"]
+        floor = link["min_h2d"] + link["min_d2h"]
+        out["residency"] = {"hbm_budget": f"{1.0 - host_fraction:.2f} of the fp32-state chunks, x (1 + {w.budget_jitter} u_t), u_t ~ U(-1, 1) seeded",
+                            "resident_chunks_per_step": link["resident_chunks"], "chunks_that_changed_residence": link["moved_chunks"],
+                            "link_bytes": moved, "link_bytes_minimum": floor, "link_bytes_over_minimum": moved / floor if floor else None}
     print(json.dumps(out))
     psx.psx_ctx_destroy(st.ctx)
 

@@ -24,7 +24,12 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).
  *     Calls enqueue work on it and return; they are asynchronous unless the
  *     description says the call synchronises.  A context must not be used
- *     from two threads at once.
+ *     from two threads at once.  Calls on one context share its descriptor
+ *     tables and flags and are ordered by the stream they are issued on:
+ *     issue them on one stream, or order different streams yourself (event
+ *     or synchronisation) before the next call on the same context.  The
+ *     calls copy descriptors with hipMemcpyAsync from buffers that later
+ *     calls reuse, so they must not be recorded into a HIP graph.
  *   - Chunk base addresses must be 16-byte aligned.  Tensor addresses need
  *     only their element alignment.
  *   - Element counts are in elements, never bytes.
@@ -46,7 +51,7 @@ extern "C" {
 #define PSX_ECAP       (-3)  /* an output array or a context table is too small       */
 #define PSX_EALIGN     (-4)  /* a chunk base is not 16-byte aligned                   */
 #define PSX_EHIP       (-5)  /* the HIP runtime reported an error (see last error)    */
-#define PSX_ENOSTAGING (-6)  /* host-resident chunk given to a context without staging */
+#define PSX_ENOSTAGING (-6)  /* PSX_TUNE_HOST_MODE 0 and a host-side chunk, but no staging   */
 
 /* Message of the last failing call on this thread ("" if none). Host pointer, owned by the library. */
 const char *psx_last_error(void);
@@ -90,7 +95,7 @@ typedef struct psx_ctx_config {
     uint64_t max_chunks;          /* most chunks any call will pass                          */
     uint64_t max_tensors;         /* most tensors any pack/unpack call will pass             */
     uint64_t staging_tile_elems;  /* elements per staging tile for host-resident chunks;     */
-                                  /* 0 = no staging (host-resident chunks are refused)       */
+                                  /* only PSX_TUNE_HOST_MODE 0 uses staging; 0 = none        */
     uint32_t staging_slots;       /* tiles in flight, 2..8 (ignored when tile_elems == 0)    */
     uint32_t reserved;            /* 0 */
 } psx_ctx_config;
@@ -202,9 +207,12 @@ typedef struct psx_adam_hyper {
  *                  device-accessible, as hipHostMalloc memory is); with
  *                  PSX_TUNE_HOST_MODE 0 they are streamed tile by tile through
  *                  the context's staging (H2D, update, D2H).  p32/m/v may be NULL.
- *   HOST -> HBM  : copied into p32/m/v, updated there (chunk admitted).
- *   HBM  -> HOST : updated in p32/m/v, then copied to the host buffers (chunk
- *                  evicted; the device buffers keep a copy the caller may drop).
+ *   HOST -> HBM  : chunk admitted: the kernel reads the pinned buffers and
+ *                  writes p32/m/v (mode 0: copied into p32/m/v, updated there).
+ *   HBM  -> HOST : chunk evicted: the kernel reads p32/m/v and writes the
+ *                  pinned buffers (mode 0: updated in p32/m/v, then copied out).
+ *                  The buffers of the home a chunk leaves hold stale or updated
+ *                  values afterwards, depending on the mode: treat them as dead.
  */
 typedef struct psx_chunk {
     void *g16;        /* device, fp16 gradients, chunk_elems capacity, first `used` read */
@@ -262,11 +270,12 @@ int32_t psx_loss_scale_update(psx_scaler *s, uint32_t overflow);
  *   PSX_TUNE_ADAM_WG_PER_CU      cap on Adam workgroups resident per CU (0 = none)
  *   PSX_TUNE_COPY_UNROLL         16-byte vectors per thread and tile of pack/unpack: 1 or 4; 0 = 4 when more
  *                                than 1024 tensors are passed, else 1 (default)
- *   PSX_TUNE_HOST_MODE           host-resident (HOST -> HOST) chunks: 0 = staged through device tiles with
- *                                H2D / D2H copies on the copy streams; 1 = the kernel reads and writes the
- *                                pinned buffers directly over the host link (they must be device-accessible,
- *                                which hipHostMalloc memory is)
- *   PSX_TUNE_HOST_GRID           mode 1: persistent workgroups of that launch
+ *   PSX_TUNE_HOST_MODE           chunks with a host side: 0 = H2D / D2H copies on the copy streams (through
+ *                                the context's staging tiles for HOST -> HOST, into / out of the device
+ *                                buffers for chunks that change residence); 1 = the kernels read and write
+ *                                the pinned buffers directly over the host link (they must be
+ *                                device-accessible, which hipHostMalloc memory is; no staging needed)
+ *   PSX_TUNE_HOST_GRID           mode 1: persistent workgroups of those launches
  *   PSX_TUNE_HOST_UNROLL         mode 1: rows of 4 elements per thread: 1, 2 or 4
  */
 #define PSX_TUNE_ADAM_BLOCKS_PER_CU 1u

@@ -31,6 +31,21 @@ struct AdamRun {
     uint32_t pad;
 };
 
+// A run whose fp32 states change residence while they are updated: read from one
+// home (p, m, v), written to the other (po, mo, vo); one of the two is pinned host
+// memory.  The home read from is left as it was.
+struct MoveRun {
+    const uint16_t *g16;
+    uint16_t *p16;
+    const float *p, *m, *v;
+    float *po, *mo, *vo;
+    uint64_t n;
+    uint64_t tile_begin;
+    uint32_t chunk;
+    uint32_t pad;
+    uint64_t pad2;
+};
+
 struct CopySeg {
     const void *src;
     void *dst;
@@ -67,6 +82,7 @@ struct Tuning {
 constexpr uint32_t kThreads = 256;
 inline uint64_t adam_tile_elems(const Tuning &t) { return (uint64_t)t.adam_threads * 4u * (uint64_t)t.adam_unroll; }
 constexpr uint64_t kRecastTileElems = (uint64_t)kThreads * 4u * 2u;
+constexpr uint64_t kMoveTileElems = (uint64_t)kThreads * 4u;
 constexpr uint64_t kCheckTileElems = (uint64_t)kThreads * 8u * 4u;   // 8192 fp16 per tile
 // Small tiles copy fastest, but every tile pays one owner search; with thousands of tensors the search
 // is deep enough that 4x larger tiles win (measured on the 5000-tensor workload).
@@ -80,6 +96,11 @@ struct RunView {
     const uint64_t *begins;
     uint32_t n;
 };
+struct MoveView {
+    const MoveRun *runs;
+    const uint64_t *begins;
+    uint32_t n;
+};
 struct SegView {
     const CopySeg *segs;
     const uint64_t *begins;
@@ -90,6 +111,10 @@ struct SegView {
 hipError_t launch_adam(const RunView &rv, uint64_t n_tiles,
                        const AdamScalars &sc, const uint32_t *flag_dev, const Tuning &t,
                        int n_cu, hipStream_t s);
+// Same update for runs that change residence, on `grid` persistent workgroups.  With *flag_dev != 0
+// the states are copied to their new home unchanged and p16 is left alone.
+hipError_t launch_adam_move(const MoveView &mv, uint64_t n_tiles, const AdamScalars &sc,
+                            const uint32_t *flag_dev, const Tuning &t, uint32_t grid, hipStream_t s);
 // skipped step with p16 aliasing g16: p16 = fp16(p32), only when *flag_dev != 0
 hipError_t launch_recast_if_flag(const RunView &rv, uint64_t n_tiles,
                                  const uint32_t *flag_dev, const Tuning &t, int n_cu, hipStream_t s);

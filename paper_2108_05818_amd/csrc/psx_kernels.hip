@@ -228,6 +228,81 @@ hipError_t launch_adam(const RunView &rv, uint64_t n_tiles, const AdamScalars &s
               : launch_adam_u<256, false>(t.adam_unroll, rv, n_tiles, sc, flag, grid, lds, s);
 }
 
+// ------------------------------------------------------------------ Adam on runs that change residence
+// The fp32 states are read from the home they leave and written to the home
+// they move to, so each crosses the host link once and no copy comes before or
+// after.  Meant for a few persistent workgroups: the link, not HBM, is the
+// bound.  On a skipped step the states still move, unchanged.
+template <bool NT, int DM>
+__global__ __launch_bounds__(kThreads) void adam_move_kernel(const MoveRun *__restrict__ runs,
+                                                             const uint64_t *__restrict__ begins,
+                                                             uint32_t n_runs, uint64_t n_tiles,
+                                                             AdamScalars sc,
+                                                             const uint32_t *__restrict__ flag) {
+    const bool skip = flag != nullptr && *flag != 0;
+    constexpr uint32_t TILE = kThreads * 4;
+    const uint32_t tid = threadIdx.x;
+    for (uint64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const uint32_t r = find_owner(begins, n_runs, tile);
+        const uint16_t *g16 = runs[r].g16;
+        uint16_t *p16 = runs[r].p16;
+        const float *pp = runs[r].p, *pm = runs[r].m, *pv = runs[r].v;
+        float *po = runs[r].po, *mo = runs[r].mo, *vo = runs[r].vo;
+        const uint64_t n = runs[r].n;
+        const uint64_t i = (tile - runs[r].tile_begin) * TILE + tid * 4;
+        if (i + 4 <= n) {
+            f32x4 p = ld<NT>(gptr<f32x4>(pp + i));
+            f32x4 m = ld<NT>(gptr<f32x4>(pm + i));
+            f32x4 v = ld<NT>(gptr<f32x4>(pv + i));
+            if (!skip) {
+                const f16x4 g = ld<NT>(gptr<f16x4>(g16 + i));
+                f16x4 h;
+#pragma unroll
+                for (int k = 0; k < 4; k++) {
+                    float pk = p[k], mk = m[k], vk = v[k];
+                    adam_elem<DM>((float)g[k], pk, mk, vk, sc);
+                    p[k] = pk; m[k] = mk; v[k] = vk;
+                    h[k] = (_Float16)pk;
+                }
+                st<NT>(gptr<f16x4>(p16 + i), h);
+            }
+            st<NT>(gptr<f32x4>(po + i), p);
+            st<NT>(gptr<f32x4>(mo + i), m);
+            st<NT>(gptr<f32x4>(vo + i), v);
+        } else {
+            for (uint64_t k = i; k < n; k++) {
+                float pk = *gptr<float>(pp + k), mk = *gptr<float>(pm + k), vk = *gptr<float>(pv + k);
+                if (!skip) {
+                    const _Float16 gk = *gptr<_Float16>(g16 + k);
+                    adam_elem<DM>((float)gk, pk, mk, vk, sc);
+                    *gptr<_Float16>(p16 + k) = (_Float16)pk;
+                }
+                *gptr<float>(po + k) = pk; *gptr<float>(mo + k) = mk; *gptr<float>(vo + k) = vk;
+            }
+        }
+    }
+}
+
+template <bool NT>
+static hipError_t launch_adam_move_nt(const MoveView &mv, uint64_t n_tiles, const AdamScalars &sc,
+                                      const uint32_t *flag, uint32_t grid, hipStream_t s) {
+    switch (sc.decay_mode) {
+        case 0: hipLaunchKernelGGL((adam_move_kernel<NT, 0>), dim3(grid), dim3(kThreads), 0, s, mv.runs, mv.begins, mv.n, n_tiles, sc, flag); break;
+        case 1: hipLaunchKernelGGL((adam_move_kernel<NT, 1>), dim3(grid), dim3(kThreads), 0, s, mv.runs, mv.begins, mv.n, n_tiles, sc, flag); break;
+        default: hipLaunchKernelGGL((adam_move_kernel<NT, 2>), dim3(grid), dim3(kThreads), 0, s, mv.runs, mv.begins, mv.n, n_tiles, sc, flag); break;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_adam_move(const MoveView &mv, uint64_t n_tiles, const AdamScalars &sc,
+                            const uint32_t *flag, const Tuning &t, uint32_t grid, hipStream_t s) {
+    if (n_tiles == 0) return hipSuccess;
+    if (grid == 0) grid = 1;
+    if ((uint64_t)grid > n_tiles) grid = (uint32_t)n_tiles;
+    return t.nontemporal ? launch_adam_move_nt<true>(mv, n_tiles, sc, flag, grid, s)
+                         : launch_adam_move_nt<false>(mv, n_tiles, sc, flag, grid, s);
+}
+
 // ------------------------------------------------------------------ re-cast on a skipped step
 // Runs with the same tiling as the Adam kernel (unroll 2).  Does work only when the
 // overflow flag is set: the fp16 chunk, which held gradients, receives fp16(p32).

@@ -103,7 +103,7 @@ struct psx_ctx {
     int n_cu = 0;
     psx_ctx_config cfg{};
     Tuning tune;
-    Table adam_tbl, check_tbl, pack_tbl, unpack_tbl;
+    Table adam_tbl, move_tbl, check_tbl, pack_tbl, unpack_tbl;
     uint32_t *flags_dev = nullptr;     // [0] global, [1 + c] chunk c
     uint32_t *flags_host = nullptr;    // pinned read-back buffer
     size_t flags_n = 0;
@@ -115,6 +115,7 @@ struct psx_ctx {
     TimedSpan t_pack, t_check, t_adam, t_spill;
     uint64_t adam_elems = 0, spill_elems = 0, h2d_bytes = 0, d2h_bytes = 0;
     std::vector<AdamRun> runs;         // scratch for table building
+    std::vector<MoveRun> moves;
     std::vector<CopySeg> segs;
     std::vector<unsigned char> blob;   // scratch: descriptors + first tiles, as uploaded
     int copy_unroll_now = 1;           // tile shape the segments in `segs` were cut for
@@ -217,6 +218,7 @@ extern "C" int32_t psx_ctx_create(const psx_ctx_config *cfg, psx_ctx **out) {
     int32_t rc;
     const size_t tiles_guess = cfg->staging_tile_elems ? 64 : 0;
     if ((rc = table_reserve(c->adam_tbl, (3 * cfg->max_chunks + tiles_guess) * (sizeof(AdamRun) + 8))) != PSX_OK) return bail(rc);
+    if ((rc = table_reserve(c->move_tbl, cfg->max_chunks * (sizeof(MoveRun) + 8))) != PSX_OK) return bail(rc);
     if ((rc = table_reserve(c->check_tbl, cfg->max_chunks * (sizeof(AdamRun) + 8))) != PSX_OK) return bail(rc);
     const size_t segs = (size_t)cfg->max_tensors + (size_t)cfg->max_chunks + 1;
     if ((rc = table_reserve(c->pack_tbl, segs * (sizeof(CopySeg) + 8))) != PSX_OK) return bail(rc);
@@ -232,7 +234,7 @@ extern "C" int32_t psx_ctx_destroy(psx_ctx *c) {
         if (e != hipSuccess && rc == PSX_OK) rc = fail(PSX_EHIP, "psx_ctx_destroy: %s -> %s", what, hipGetErrorString(e));
     };
     note(hipDeviceSynchronize(), "hipDeviceSynchronize");
-    for (Table *t : {&c->adam_tbl, &c->check_tbl, &c->pack_tbl, &c->unpack_tbl}) {
+    for (Table *t : {&c->adam_tbl, &c->move_tbl, &c->check_tbl, &c->pack_tbl, &c->unpack_tbl}) {
         int32_t r = table_free(*t);
         if (r != PSX_OK && rc == PSX_OK) rc = r;
     }
@@ -701,8 +703,7 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
         if (host_side) {
             if (!ch.p32_host || !ch.m_host || !ch.v_host) return fail(PSX_EINVAL, "psx_chunk_adam_step: chunk %zu needs pinned p32/m/v", k);
             if (!aligned16(ch.p32_host) || !aligned16(ch.m_host) || !aligned16(ch.v_host)) return fail(PSX_EALIGN, "psx_chunk_adam_step: chunk %zu host states not 16-byte aligned", k);
-            const bool staged = ch.exec != PSX_EXEC_CPU &&
-                                !(c->tune.host_mode == 1 && ch.loc_in == PSX_LOC_HOST && ch.loc_out == PSX_LOC_HOST);
+            const bool staged = ch.exec != PSX_EXEC_CPU && c->tune.host_mode != 1;
             if (staged && T == 0) return fail(PSX_ENOSTAGING, "psx_chunk_adam_step: chunk %zu is host-resident but the context has no staging", k);
             if (!staged && ch.exec != PSX_EXEC_CPU) {
                 // the kernel will dereference these host pointers: they must be page-locked memory the
@@ -781,9 +782,9 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
             continue;
         }
         spill_elems += ch.used;
-        if (direct && in_host && out_host) {          // handled below: the kernel works on the host buffers
-            h2d_bytes += 3 * ch.used * sizeof(float);
-            d2h_bytes += 3 * ch.used * sizeof(float);
+        if (direct) {                                 // handled below: the kernels work on the host buffers
+            if (in_host) h2d_bytes += 3 * ch.used * sizeof(float);
+            if (out_host) d2h_bytes += 3 * ch.used * sizeof(float);
             continue;
         }
         for (uint64_t off = 0; off < ch.used; off += T) {
@@ -821,8 +822,9 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
     td.grid_override = c->tune.host_grid;
     const uint64_t direct_tile = adam_tile_elems(td);
     const size_t direct_off = c->runs.size();
-    uint64_t direct_tiles = 0, direct_recast_tiles = 0;
+    uint64_t direct_tiles = 0, direct_recast_tiles = 0, move_tiles = 0;
     size_t n_direct = 0, n_direct_recast = 0;
+    c->moves.clear();
     if (direct) {
         for (size_t k = 0; k < n_chunks; k++) {
             const psx_chunk &ch = chunks[k];
@@ -830,11 +832,33 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
             direct_tiles += push_run(c->runs, ch.g16, ch.p16, ch.p32_host, ch.m_host, ch.v_host, ch.used, direct_tiles, direct_tile, (uint32_t)k);
         }
         n_direct = c->runs.size() - direct_off;
+        // chunks that change residence: read from the home they leave, written to the one they move to
+        for (size_t k = 0; k < n_chunks; k++) {
+            const psx_chunk &ch = chunks[k];
+            if (ch.used == 0 || ch.loc_in == ch.loc_out) continue;
+            const bool in_host = ch.loc_in == PSX_LOC_HOST;
+            MoveRun r{};
+            r.g16 = static_cast<const uint16_t *>(ch.g16);
+            r.p16 = static_cast<uint16_t *>(ch.p16);
+            r.p = static_cast<const float *>(in_host ? ch.p32_host : ch.p32);
+            r.m = static_cast<const float *>(in_host ? ch.m_host : ch.m);
+            r.v = static_cast<const float *>(in_host ? ch.v_host : ch.v);
+            r.po = static_cast<float *>(in_host ? ch.p32 : ch.p32_host);
+            r.mo = static_cast<float *>(in_host ? ch.m : ch.m_host);
+            r.vo = static_cast<float *>(in_host ? ch.v : ch.v_host);
+            r.n = ch.used; r.tile_begin = move_tiles; r.chunk = (uint32_t)k;
+            c->moves.push_back(r);
+            move_tiles += (ch.used + kMoveTileElems - 1) / kMoveTileElems;
+        }
+        // skipped step with the gradients in the fp16 parameter chunk: the parameters are cast back from
+        // the home the states were read from (a skipped step leaves it valid)
         if (use_flag)
             for (size_t k = 0; k < n_chunks; k++) {
                 const psx_chunk &ch = chunks[k];
-                if (ch.used == 0 || ch.loc_in != PSX_LOC_HOST || ch.loc_out != PSX_LOC_HOST || ch.g16 != ch.p16 || ch.exec == PSX_EXEC_CPU) continue;
-                direct_recast_tiles += push_run(c->runs, ch.g16, ch.p16, ch.p32_host, ch.m_host, ch.v_host, ch.used, direct_recast_tiles, recast_tile, (uint32_t)k);
+                if (ch.used == 0 || (ch.loc_in == PSX_LOC_HBM && ch.loc_out == PSX_LOC_HBM) || ch.g16 != ch.p16 || ch.exec == PSX_EXEC_CPU) continue;
+                const bool in_host = ch.loc_in == PSX_LOC_HOST;
+                direct_recast_tiles += push_run(c->runs, ch.g16, ch.p16, in_host ? ch.p32_host : ch.p32, in_host ? ch.m_host : ch.m,
+                                                in_host ? ch.v_host : ch.v, ch.used, direct_recast_tiles, recast_tile, (uint32_t)k);
             }
         n_direct_recast = c->runs.size() - direct_off - n_direct;
     }
@@ -842,6 +866,9 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
     const AdamRun *tbl = nullptr;
     const uint64_t *tbl_begins = nullptr;
     if ((rc = upload_described(c->adam_tbl, c->runs, c->blob, s, &tbl, &tbl_begins)) != PSX_OK) return rc;
+    const MoveRun *mtbl = nullptr;
+    const uint64_t *mtbl_begins = nullptr;
+    if (!c->moves.empty() && (rc = upload_described(c->move_tbl, c->moves, c->blob, s, &mtbl, &mtbl_begins)) != PSX_OK) return rc;
     auto view = [&](size_t off, size_t n) { return RunView{tbl + off, tbl_begins + off, (uint32_t)n}; };
     const uint32_t *flag = use_flag ? c->flags_dev : nullptr;
 
@@ -856,7 +883,7 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
     // ---- the side streams may start once earlier work on the caller's stream (and the check) is done
     const bool any_cpu = !cpu_tiles.empty();
     if (any_cpu && (rc = ensure_cpu(c)) != PSX_OK) return rc;
-    const bool any_side = !tiles.empty() || n_direct != 0 || any_cpu;
+    const bool any_side = !tiles.empty() || n_direct != 0 || move_tiles != 0 || any_cpu;
     c->t_spill.valid = false;
     if (any_side) {
         PSX_HIP(hipEventRecord(c->ev_entry, s));
@@ -886,8 +913,12 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
     // the resident launch; every load and store of p/m/v crosses the host link once, in both directions at once
     c->spill_elems = spill_elems; c->h2d_bytes = h2d_bytes; c->d2h_bytes = d2h_bytes;
     bool any_h2d = false, any_d2h = false;
-    if (n_direct != 0) {
-        PSX_HIP(launch_adam(view(direct_off, n_direct), direct_tiles, sc, flag, td, c->n_cu, c->h2d));
+    if (n_direct != 0 || move_tiles != 0) {
+        if (n_direct != 0)
+            PSX_HIP(launch_adam(view(direct_off, n_direct), direct_tiles, sc, flag, td, c->n_cu, c->h2d));
+        if (move_tiles != 0)
+            PSX_HIP(launch_adam_move(MoveView{mtbl, mtbl_begins, (uint32_t)c->moves.size()}, move_tiles, sc, flag, c->tune,
+                                     (uint32_t)c->tune.host_grid, c->h2d));
         if (n_direct_recast != 0)
             PSX_HIP(launch_recast_if_flag(view(direct_off + n_direct, n_direct_recast), direct_recast_tiles, flag, td, c->n_cu, c->h2d));
         any_h2d = true;

@@ -360,6 +360,52 @@ def test_host_resident_chunks_stream_through_staging(orc, alias, slots, mode):
         psx.psx_ctx_destroy(ctx)
 
 
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("alias", [False, True])
+def test_skipped_step_still_moves_chunks_that_change_residence(orc, alias, mode):
+    """An overflow skips the update, but a chunk admitted to or evicted from HBM in that step must still
+    find its fp32 states, bit for bit, in the new home; aliased fp16 chunks get their parameters back."""
+    ctx = psx.psx_ctx_create(max_chunks=8, max_tensors=4, staging_tile_elems=4096, staging_slots=2)
+    psx.psx_ctx_set_tuning(ctx, psx.PSX_TUNE_HOST_MODE, mode)
+    psx.psx_ctx_set_tuning(ctx, psx.PSX_TUNE_HOST_GRID, 5)
+    try:
+        used = [5000, 4097, 1, 9000, 12288]
+        loc = [(G, G), (H, G), (G, H), (H, H), (G, H)]
+        Cn = 12288
+        cl = ChunkLists(used, Cn, alias=alias)
+        fill_state(cl, 8800, 1024.0, zero_mv=False)
+        host = []
+        for k in range(cl.n):
+            hs = [torch.from_numpy(sent32(Cn)).pin_memory() for _ in range(3)]
+            if loc[k][0] == H:
+                for hbuf, name in zip(hs, ("p32", "m", "v")):
+                    hbuf.copy_(torch.from_numpy(cl.np[name][k]))
+                    getattr(cl, name)[k][:used[k]].view(torch.int32).fill_(0x0BADBEEF)    # device copy is garbage
+            host.append(hs)
+        cl.set("g16", 3, np.array([0xFC00], np.uint16), at=8999)
+        hp = dict(lr=1e-3, weight_decay=0.01, step=3, loss_scale=1024.0)
+        psx.psx_chunk_adam_step(ctx, psx.make_chunks(cl.specs(loc=loc, host=host)), psx.make_hyper(**hp),
+                                psx.PSX_STEP_CHECK_FIRST)
+        flag, per = psx.psx_overflow_read(ctx, len(used))
+        torch.cuda.synchronize()
+        assert flag == 1 == cl.oracle_step(orc, orc.hyper(**hp)) and list(per) == [0, 0, 0, 1, 0]
+        where = [host[k] if loc[k][1] == H else None for k in range(cl.n)]
+        assert cl.compare("skipped, moved", where=where) == 0.0
+        # and the step after it, now finite, runs from the new homes
+        cl.set("g16", 3, np.array([0x3C00], np.uint16), at=8999)
+        if alias:                                    # the fp16 chunks hold parameters again: new gradients
+            for k in range(cl.n):
+                cl.set("g16", k, W.grads_f16_np(used[k], 8900 + k, 1024.0))
+        loc = [(b, b) for (_, b) in loc]
+        psx.psx_chunk_adam_step(ctx, psx.make_chunks(cl.specs(loc=loc, host=host)), psx.make_hyper(**hp),
+                                psx.PSX_STEP_CHECK_FIRST)
+        torch.cuda.synchronize()
+        assert cl.oracle_step(orc, orc.hyper(**hp)) == 0
+        assert cl.compare("after the skipped step", where=where) == 0.0
+    finally:
+        psx.psx_ctx_destroy(ctx)
+
+
 def test_bad_arguments_touch_nothing():
     ctx = psx.psx_ctx_create(max_chunks=4, max_tensors=4)
     try:
@@ -371,10 +417,10 @@ def test_bad_arguments_touch_nothing():
         with pytest.raises(psx.PsxError) as e:
             psx.psx_chunk_adam_step(ctx, psx.make_chunks(cl.specs(loc=[(H, H)], host=[hs])), psx.make_hyper())
         assert e.value.code == psx.PSX_ENOSTAGING
-        psx.psx_ctx_set_tuning(ctx, psx.PSX_TUNE_HOST_MODE, 1)
         with pytest.raises(psx.PsxError) as e:
             psx.psx_chunk_adam_step(ctx, psx.make_chunks(cl.specs(loc=[(H, G)], host=[hs])), psx.make_hyper())
         assert e.value.code == psx.PSX_ENOSTAGING
+        psx.psx_ctx_set_tuning(ctx, psx.PSX_TUNE_HOST_MODE, 1)
         # direct access to host states that are not page-locked would fault the GPU: refused up front
         pageable = [torch.zeros(64) for _ in range(3)]
         with pytest.raises(psx.PsxError) as e:
