@@ -25,6 +25,41 @@ def test_library_exports_every_declared_symbol():
         assert getattr(L, name) is not None
 
 
+def test_header_is_plain_c_and_binding_structs_match_it(tmp_path):
+    """include/psx.h must compile as strict C99 on its own, and every struct of the Python binding must have
+    the size and field offsets the C compiler gives it (a marshalling mismatch would corrupt arguments
+    silently).  Constants the binding repeats are compared as well."""
+    import subprocess
+    structs = [psx.psx_slot, psx.psx_ctx_config, psx.psx_adam_hyper, psx.psx_chunk, psx.psx_scaler,
+               psx.psx_timing, psx.psx_link_rates]
+    consts = [n for n in dir(psx) if n.startswith("PSX_") and isinstance(getattr(psx, n), int)]
+    header = open(os.path.join(ROOT, "include", "psx.h")).read()
+    consts = [n for n in consts if re.search(r"#define\s+%s\b" % n, header)]
+    assert len(consts) > 25
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "psx.h"', 'int main(void) {']
+    for st in structs:
+        n = st.__name__
+        lines.append(f'printf("{n} %zu\\n", sizeof({n}));')
+        for f, _ in st._fields_:
+            lines.append(f'printf("{n}.{f} %zu\\n", offsetof({n}, {f}));')
+    for n in consts:
+        lines.append(f'printf("{n} %lld\\n", (long long)({n}));')
+    lines.append('return 0; }')
+    src = tmp_path / "abi.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "abi"
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", str(exe)], check=True)
+    got = dict(l.split() for l in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.splitlines())
+    for st in structs:
+        n = st.__name__
+        assert int(got[n]) == C.sizeof(st), n
+        for f, _ in st._fields_:
+            assert int(got[f"{n}.{f}"]) == getattr(st, f).offset, f"{n}.{f}"
+    for n in consts:
+        assert int(got[n]) == getattr(psx, n), n
+
+
 def _same_layout(orc, numel, C_, flags=0):
     o_slots, o_used = orc.chunk_layout(numel, C_, strict=bool(flags & psx.PSX_LAYOUT_STRICT))
     slots, used = psx.psx_chunk_layout(numel, C_, flags)
