@@ -296,7 +296,7 @@ def main():
                  "cunroll": psx.PSX_TUNE_COPY_UNROLL, "hostmode": psx.PSX_TUNE_HOST_MODE,
                  "hostgrid": psx.PSX_TUNE_HOST_GRID, "hostunroll": psx.PSX_TUNE_HOST_UNROLL,
                  "cputhreads": psx.PSX_TUNE_CPU_THREADS, "cputile": psx.PSX_TUNE_CPU_TILE_ELEMS,
-                 "cpuisa": psx.PSX_TUNE_CPU_ISA}
+                 "cpuisa": psx.PSX_TUNE_CPU_ISA, "cthreads": psx.PSX_TUNE_COPY_THREADS}
     for kv in filter(None, a.tune.split(",")):
         k, v = kv.split("=")
         psx.psx_ctx_set_tuning(st.ctx, tune_keys[k], int(v))
@@ -346,6 +346,20 @@ def main():
     achieved = adam_bytes / (phase["adam_ms"] * 1e-3) / 1e9 if phase["adam_ms"] > 0 else 0.0
     traffic = read_traffic(os.path.join(ROOT, "profiles", "adam_kernel_gpt1b_hbm_traffic.txt")) \
         if (a.workload == "gpt1b" and not a.layers and not a.chunk_elems and host_fraction == 0) else None
+    # a same-run yardstick for the roofline: this library's plain copy kernel over 1 GiB (1 read + 1 write stream)
+    nb = 1 << 30
+    src = torch.ones(nb // 4, dtype=torch.float32, device=dev)
+    dst = torch.zeros_like(src)
+    for _ in range(3):
+        psx.psx_copy_bytes(st.ctx, dst, src, nb)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(10):
+        psx.psx_copy_bytes(st.ctx, dst, src, nb)         # launched on torch's current stream, as the events are
+    e1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 10 * 2 * nb / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del src, dst
     out = {
         "metric": "chunked Adam Gelem/s (whole hot path per step: layout + grad pack + overflow check + fused Adam + fp16 unpack + loss-scale update)",
         "value": n_elems / (ms * 1e-3) / 1e9,
@@ -360,7 +374,8 @@ def main():
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "kernel": "psx::adam_kernel (resident chunks, one launch)",
-                     "bytes_per_launch": adam_bytes, "avg_launch_ms": phase["adam_ms"]},
+                     "bytes_per_launch": adam_bytes, "avg_launch_ms": phase["adam_ms"],
+                     "same_run_plain_copy_GBs": copy_gbs, "frac_of_plain_copy": achieved / copy_gbs},
         "adam_only_gelem_s": adam_elems / (phase["adam_ms"] * 1e-3) / 1e9 if phase["adam_ms"] > 0 else None,
         "phase_ms": phase,
         "cpu_baseline": cpu,

@@ -270,6 +270,7 @@ int32_t psx_loss_scale_update(psx_scaler *s, uint32_t overflow);
  *   PSX_TUNE_ADAM_WG_PER_CU      cap on Adam workgroups resident per CU (0 = none)
  *   PSX_TUNE_COPY_UNROLL         16-byte vectors per thread and tile of pack/unpack: 1 or 4; 0 = 4 when more
  *                                than 1024 tensors are passed, else 1 (default)
+ *   PSX_TUNE_COPY_THREADS        threads per workgroup of pack/unpack: 64 (default) or 256
  *   PSX_TUNE_HOST_MODE           chunks with a host side: 0 = H2D / D2H copies on the copy streams (through
  *                                the context's staging tiles for HOST -> HOST, into / out of the device
  *                                buffers for chunks that change residence); 1 = the kernels read and write
@@ -291,6 +292,7 @@ int32_t psx_loss_scale_update(psx_scaler *s, uint32_t overflow);
 #define PSX_TUNE_CPU_THREADS        11u  /* worker threads for PSX_EXEC_CPU chunks (default: min(cores, 16)) */
 #define PSX_TUNE_CPU_TILE_ELEMS     12u  /* elements per tile of the PSX_EXEC_CPU pipeline (multiple of 16)  */
 #define PSX_TUNE_CPU_ISA            13u  /* PSX_EXEC_CPU vectors: 0 = widest the host has (AVX-512, else AVX2), 1 = AVX2 */
+#define PSX_TUNE_COPY_THREADS       14u
 int32_t psx_ctx_set_tuning(psx_ctx *ctx, uint32_t key, int64_t value);
 
 /* Kernel timing with HIP events on the caller's stream (off by default). */

@@ -69,6 +69,7 @@ struct Tuning {
     int nontemporal = 1;
     int copy_blocks_per_cu = 0;
     int copy_unroll = 0;           // 16-byte vectors per thread and tile of pack/unpack: 1 or 4; 0 = by tensor count
+    int copy_threads = 64;         // threads per workgroup of pack/unpack: 64 or 256
     int host_mode = 1;             // host-resident chunks: 0 staged H2D/kernel/D2H, 1 kernel works on pinned memory
     int host_grid = 32;            // direct mode: persistent workgroups (256 threads) of the host launch
     int host_unroll = 1;           // direct mode: rows of 4 elements per thread
@@ -84,10 +85,11 @@ inline uint64_t adam_tile_elems(const Tuning &t) { return (uint64_t)t.adam_threa
 constexpr uint64_t kRecastTileElems = (uint64_t)kThreads * 4u * 2u;
 constexpr uint64_t kMoveTileElems = (uint64_t)kThreads * 4u;
 constexpr uint64_t kCheckTileElems = (uint64_t)kThreads * 8u * 4u;   // 8192 fp16 per tile
-// Small tiles copy fastest, but every tile pays one owner search; with thousands of tensors the search
+// Small tiles of one wavefront copy fastest (measured: 6.7 TB/s against 6.3 with 256 threads), but every tile
+// pays one owner search; with thousands of tensors the search
 // is deep enough that 4x larger tiles win (measured on the 5000-tensor workload).
 inline int copy_unroll_for(const Tuning &t, size_t n_tensors) { return t.copy_unroll != 0 ? t.copy_unroll : (n_tensors > 1024 ? 4 : 1); }
-inline uint64_t copy_tile_bytes(int unroll) { return (uint64_t)kThreads * 16u * (uint64_t)(unroll == 1 ? 1 : 4); }
+inline uint64_t copy_tile_bytes(const Tuning &t, int unroll) { return (uint64_t)(t.copy_threads == 64 ? 64 : 256) * 16u * (uint64_t)(unroll == 1 ? 1 : 4); }
 
 // A section of a descriptor table on the device: n descriptors and, in a dense array of its own,
 // the first tile of each (what the kernels search to find the owner of a tile).

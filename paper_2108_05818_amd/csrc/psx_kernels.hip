@@ -437,13 +437,13 @@ __device__ __forceinline__ uint32_t test_vec(const u32x4 &w) {
         return 0;
 }
 
-template <int ES, bool CHECK, bool NT, int U>
-__global__ __launch_bounds__(kThreads) void copy_kernel(const CopySeg *__restrict__ segs,
+template <int ES, bool CHECK, bool NT, int U, int T>
+__global__ __launch_bounds__(T) void copy_kernel(const CopySeg *__restrict__ segs,
                                                         const uint64_t *__restrict__ begins,
                                                         uint32_t n_segs, uint64_t n_tiles,
                                                         uint32_t *flag, uint32_t *per_chunk) {
     typedef typename ElemT<ES>::type E;
-    constexpr uint32_t TILE_BYTES = kThreads * 16u * U;
+    constexpr uint32_t TILE_BYTES = T * 16u * U;
     constexpr uint32_t TILE_ELEMS = TILE_BYTES / ES;
     const uint32_t tid = threadIdx.x;
     for (uint64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
@@ -463,11 +463,11 @@ __global__ __launch_bounds__(kThreads) void copy_kernel(const CopySeg *__restric
             u32x4 w[U];
 #pragma unroll
             for (int u = 0; u < U; u++)
-                w[u] = ld<NT>(gptr<u32x4>(s) + u * kThreads + tid);
+                w[u] = ld<NT>(gptr<u32x4>(s) + u * T + tid);
 #pragma unroll
             for (int u = 0; u < U; u++) {
                 bad |= test_vec<ES, CHECK>(w[u]);
-                st<NT>(gptr<u32x4>(d) + u * kThreads + tid, w[u]);
+                st<NT>(gptr<u32x4>(d) + u * T + tid, w[u]);
             }
         } else {
             const uint32_t head_e = head / ES;
@@ -480,7 +480,7 @@ __global__ __launch_bounds__(kThreads) void copy_kernel(const CopySeg *__restric
             unsigned char *db = d + head;
             const uint32_t nvec = (nbytes - head) / 16u;
             if (mis == 0) {
-                for (uint32_t i = tid; i < nvec; i += kThreads) {
+                for (uint32_t i = tid; i < nvec; i += T) {
                     u32x4 w = gptr<u32x4>(sb)[i];
                     bad |= test_vec<ES, CHECK>(w);
                     gptr<u32x4>(db)[i] = w;
@@ -492,7 +492,7 @@ __global__ __launch_bounds__(kThreads) void copy_kernel(const CopySeg *__restric
                 // source bytes (never a page the tensor does not touch).
                 const PSX_GLOBAL u32x4 *ab = gptr<u32x4>(sb - mis);
                 const uint32_t q = mis >> 2, b = mis & 3u;      // whole words and bytes to drop (uniform per tile)
-                for (uint32_t i = tid; i < nvec; i += kThreads) {
+                for (uint32_t i = tid; i < nvec; i += T) {
                     const u32x4 lo = ab[i], hi = ab[i + 1];
                     uint32_t d[9] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3], 0u};
                     u32x4 w;
@@ -536,14 +536,19 @@ hipError_t launch_copy(const SegView &sv, uint64_t n_tiles, uint32_t elem_size,
     const uint32_t grid = grid_for(n_tiles, t.copy_blocks_per_cu, n_cu);
     const bool check = flag != nullptr;
     const bool nt = t.nontemporal != 0;
-#define PSX_LAUNCH_COPY(ES, CH, NT_)                                                                          \
+#define PSX_LAUNCH_COPY_T(ES, CH, NT_, T_)                                                                    \
     do {                                                                                                      \
         if (t.copy_unroll == 1)                                                                               \
-            hipLaunchKernelGGL((copy_kernel<ES, CH, NT_, 1>), dim3(grid), dim3(kThreads), 0, s, sv.segs,      \
+            hipLaunchKernelGGL((copy_kernel<ES, CH, NT_, 1, T_>), dim3(grid), dim3(T_), 0, s, sv.segs,        \
                                sv.begins, sv.n, n_tiles, flag, per_chunk);                                    \
         else                                                                                                  \
-            hipLaunchKernelGGL((copy_kernel<ES, CH, NT_, 4>), dim3(grid), dim3(kThreads), 0, s, sv.segs,      \
+            hipLaunchKernelGGL((copy_kernel<ES, CH, NT_, 4, T_>), dim3(grid), dim3(T_), 0, s, sv.segs,        \
                                sv.begins, sv.n, n_tiles, flag, per_chunk);                                    \
+    } while (0)
+#define PSX_LAUNCH_COPY(ES, CH, NT_)                                                                          \
+    do {                                                                                                      \
+        if (t.copy_threads == 64) PSX_LAUNCH_COPY_T(ES, CH, NT_, 64);                                         \
+        else PSX_LAUNCH_COPY_T(ES, CH, NT_, 256);                                                             \
     } while (0)
     if (elem_size == 2) {
         if (check) { if (nt) PSX_LAUNCH_COPY(2, true, true); else PSX_LAUNCH_COPY(2, true, false); }
@@ -551,6 +556,7 @@ hipError_t launch_copy(const SegView &sv, uint64_t n_tiles, uint32_t elem_size,
     } else {
         if (nt) PSX_LAUNCH_COPY(4, false, true); else PSX_LAUNCH_COPY(4, false, false);
     }
+#undef PSX_LAUNCH_COPY_T
 #undef PSX_LAUNCH_COPY
     return hipGetLastError();
 }
@@ -570,26 +576,17 @@ hipError_t launch_fill_u32(uint32_t *dst, uint64_t n, uint32_t value, hipStream_
     return hipGetLastError();
 }
 
+// Plain copy in the launch shape that copies fastest on this chip (found by measurement): one wavefront
+// per workgroup, one 16-byte vector per lane, tiles handed out in order, no cap on resident workgroups
+// (with only two streams per workgroup, unlike the Adam kernel's eight, a cap starves the memory system).
 template <bool NT>
-__global__ __launch_bounds__(kThreads) void copy_bytes_kernel(u32x4 *__restrict__ dst,
-                                                              const u32x4 *__restrict__ src,
-                                                              uint64_t nvec) {
-    constexpr uint32_t TILE = kThreads * 4;
-    const uint64_t n_tiles = (nvec + TILE - 1) / TILE;
+__global__ __launch_bounds__(64) void copy_bytes_kernel(u32x4 *__restrict__ dst,
+                                                        const u32x4 *__restrict__ src,
+                                                        uint64_t nvec) {
+    const uint64_t n_tiles = (nvec + 63) / 64;
     for (uint64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-        const uint64_t base = tile * TILE + threadIdx.x;
-        if (base - threadIdx.x + TILE <= nvec) {
-            u32x4 w[4];
-#pragma unroll
-            for (int u = 0; u < 4; u++) w[u] = ld<NT>(gptr<u32x4>(src + base + u * kThreads));
-#pragma unroll
-            for (int u = 0; u < 4; u++) st<NT>(gptr<u32x4>(dst + base + u * kThreads), w[u]);
-        } else {
-            for (int u = 0; u < 4; u++) {
-                const uint64_t i = base + u * kThreads;
-                if (i < nvec) dst[i] = src[i];
-            }
-        }
+        const uint64_t i = tile * 64 + threadIdx.x;
+        if (i < nvec) st<NT>(gptr<u32x4>(dst + i), ld<NT>(gptr<u32x4>(src + i)));
     }
 }
 
@@ -597,13 +594,13 @@ hipError_t launch_copy_bytes(void *dst, const void *src, uint64_t n_bytes, const
                              hipStream_t s) {
     const uint64_t nvec = n_bytes / 16;
     if (nvec == 0) return hipSuccess;
-    const uint64_t n_tiles = (nvec + kThreads * 4 - 1) / (kThreads * 4);
+    const uint64_t n_tiles = (nvec + 63) / 64;
     const uint32_t grid = grid_for(n_tiles, t.copy_blocks_per_cu, n_cu);
     if (t.nontemporal)
-        hipLaunchKernelGGL(copy_bytes_kernel<true>, dim3(grid), dim3(kThreads), 0, s,
+        hipLaunchKernelGGL(copy_bytes_kernel<true>, dim3(grid), dim3(64), 0, s,
                            static_cast<u32x4 *>(dst), static_cast<const u32x4 *>(src), nvec);
     else
-        hipLaunchKernelGGL(copy_bytes_kernel<false>, dim3(grid), dim3(kThreads), 0, s,
+        hipLaunchKernelGGL(copy_bytes_kernel<false>, dim3(grid), dim3(64), 0, s,
                            static_cast<u32x4 *>(dst), static_cast<const u32x4 *>(src), nvec);
     return hipGetLastError();
 }

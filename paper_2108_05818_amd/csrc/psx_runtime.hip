@@ -288,6 +288,10 @@ extern "C" int32_t psx_ctx_set_tuning(psx_ctx *c, uint32_t key, int64_t value) {
             if (value != 0 && value != 1 && value != 4) return fail(PSX_EINVAL, "copy unroll must be 0 (by tensor count), 1 or 4");
             c->tune.copy_unroll = (int)value;
             break;
+        case PSX_TUNE_COPY_THREADS:
+            if (value != 64 && value != 256) return fail(PSX_EINVAL, "copy threads must be 64 or 256");
+            c->tune.copy_threads = (int)value;
+            break;
         case PSX_TUNE_HOST_MODE:
             if (value != 0 && value != 1) return fail(PSX_EINVAL, "host mode must be 0 (staged copies) or 1 (direct access)");
             c->tune.host_mode = (int)value;
@@ -443,7 +447,7 @@ int32_t build_segments(psx_ctx *c, const char *who, uint32_t dtype, const void *
     if (n > c->cfg.max_tensors) return fail(PSX_ECAP, "%s: %zu tensors, context holds %llu", who, n, (unsigned long long)c->cfg.max_tensors);
     const uint32_t es = dtype == PSX_F16 ? 2u : 4u;
     c->copy_unroll_now = copy_unroll_for(c->tune, n);
-    const uint64_t tile_elems = copy_tile_bytes(c->copy_unroll_now) / es;
+    const uint64_t tile_elems = copy_tile_bytes(c->tune, c->copy_unroll_now) / es;
     const uint64_t total = (uint64_t)n_chunks * chunk_elems;
     for (size_t k = 0; k < n_chunks; k++) {
         if (chunks[k] == nullptr) return fail(PSX_EINVAL, "%s: chunk %zu is NULL", who, k);

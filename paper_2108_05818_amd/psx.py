@@ -23,6 +23,7 @@ PSX_TUNE_ADAM_BLOCKS_PER_CU, PSX_TUNE_ADAM_UNROLL, PSX_TUNE_NONTEMPORAL, PSX_TUN
 PSX_TUNE_ADAM_THREADS, PSX_TUNE_ADAM_WG_PER_CU, PSX_TUNE_COPY_UNROLL = 5, 6, 7
 PSX_TUNE_HOST_MODE, PSX_TUNE_HOST_GRID, PSX_TUNE_HOST_UNROLL = 8, 9, 10
 PSX_TUNE_CPU_THREADS, PSX_TUNE_CPU_TILE_ELEMS, PSX_TUNE_CPU_ISA = 11, 12, 13
+PSX_TUNE_COPY_THREADS = 14
 
 EXPORTS = [
     "psx_last_error", "psx_chunk_layout", "psx_ctx_create", "psx_ctx_destroy", "psx_pack", "psx_unpack",

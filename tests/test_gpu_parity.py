@@ -101,8 +101,34 @@ def test_config1_tiny_gpt_ten_steps(orc, ctx, alias):
 
 # ---------------------------------------------------------------------------------- pack / unpack
 
+COPY_SHAPES = [(64, 0, 0, 1), (256, 1, 0, 1), (64, 4, 0, 0), (256, 4, 2, 1), (64, 1, 1, 0)]
+COPY_KEYS = [psx.PSX_TUNE_COPY_THREADS, psx.PSX_TUNE_COPY_UNROLL, psx.PSX_TUNE_COPY_BLOCKS_PER_CU, psx.PSX_TUNE_NONTEMPORAL]
+
+
+class copy_shape:
+    """Select a pack/unpack launch shape (threads, vectors per thread, persistent workgroups per CU,
+    non-temporal) on the shared context for the length of a with-block; COPY_SHAPES[0] is the default."""
+
+    def __init__(self, ctx, shape):
+        self.ctx, self.shape = ctx, shape
+
+    def __enter__(self):
+        for key, val in zip(COPY_KEYS, self.shape):
+            psx.psx_ctx_set_tuning(self.ctx, key, val)
+
+    def __exit__(self, *exc):
+        for key, val in zip(COPY_KEYS, COPY_SHAPES[0]):
+            psx.psx_ctx_set_tuning(self.ctx, key, val)
+
+
+@pytest.mark.parametrize("shape", COPY_SHAPES)
 @pytest.mark.parametrize("dtype", [psx.PSX_F16, psx.PSX_F32])
-def test_pack_unpack_ragged_unaligned(orc, ctx, dtype):
+def test_pack_unpack_ragged_unaligned(orc, ctx, dtype, shape):
+    with copy_shape(ctx, shape):
+        _pack_unpack_ragged_unaligned(orc, ctx, dtype)
+
+
+def _pack_unpack_ragged_unaligned(orc, ctx, dtype):
     rng = np.random.default_rng(77)
     Cn = 20000
     numel = [1, 3, 0, 7, 8, 9, 8191, 8193, 1, 16384, 2, 45001, 5, 19999, 20000, 1, 61234, 33, 4095, 1, 1, 12345, 8192]
@@ -142,7 +168,13 @@ def test_pack_unpack_ragged_unaligned(orc, ctx, dtype):
     assert not out_big.cpu().numpy()[mask].any()
 
 
-def test_pack_with_fused_overflow_check(orc, ctx):
+@pytest.mark.parametrize("shape", COPY_SHAPES)
+def test_pack_with_fused_overflow_check(orc, ctx, shape):
+    with copy_shape(ctx, shape):
+        _pack_with_fused_overflow_check(orc, ctx)
+
+
+def _pack_with_fused_overflow_check(orc, ctx):
     Cn = 30000
     numel = [1, 17, 29999, 30000, 5, 70001, 12, 8192, 1]
     slots, used = psx.psx_chunk_layout(numel, Cn)
