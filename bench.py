@@ -40,6 +40,9 @@ def parse():
     ap.add_argument("--chunk-elems", type=int, default=0, help="override the chunk size (elements)")
     ap.add_argument("--host-fraction", type=float, default=-1.0, help="share of chunks whose fp32 states live in pinned host memory")
     ap.add_argument("--cpu-share", type=float, default=0.0, help="share of the host-resident chunks updated by the host cores instead of the GPU")
+    ap.add_argument("--chunk-reuse", action="store_true",
+                    help="the paper's chunk reuse: gradients are packed into the fp16 parameter chunks and overwritten "
+                         "there by the new parameters (default: a gradient chunk list of its own)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="also launch psx_copy_bytes once over this many MiB (a plain copy of known size, "
@@ -56,7 +59,7 @@ class State:
 
 
 def setup(w, dev, host_fraction=0.0, staging_tile_elems=4 << 20, staging_slots=3, keep_params="all", cpu_share=0.0,
-          plans=None):
+          plans=None, chunk_reuse=False):
     """Allocate chunk lists and seeded inputs on the device (and pinned host memory for
     host-resident chunks); pack the fp32 params tensor by tensor; m = v = 0.
     keep_params: "all" keeps every fp32 source tensor, an int keeps only the first that many, a set keeps
@@ -97,7 +100,7 @@ def setup(w, dev, host_fraction=0.0, staging_tile_elems=4 << 20, staging_slots=3
         arena = torch.zeros(C * max(n, 1), dtype=dtype, device=dev)
         return [arena[k * C:(k + 1) * C] for k in range(n)]
     st.p16 = chunk_list(torch.float16, st.nch)
-    st.g16 = chunk_list(torch.float16, st.nch)
+    st.g16 = st.p16 if chunk_reuse else chunk_list(torch.float16, st.nch)
     # fp32 states: device homes (one arena per list over the chunks that are ever HBM-resident) and
     # pinned host homes (for the chunks that are ever host-resident)
     p_list, m_list, v_list = (iter(chunk_list(torch.float32, sum(need_dev))) for _ in range(3))
@@ -289,7 +292,7 @@ def main():
     # the fp32 source tensors are needed again only by the oracle leg, and only the first few of them
     st = setup(w, dev, host_fraction, a.staging_tile, a.staging_slots,
                keep_params=0 if a.no_cpu_baseline else CPU_BASELINE_TENSORS,
-               cpu_share=0.0 if plans else a.cpu_share, plans=plans)
+               cpu_share=0.0 if plans else a.cpu_share, plans=plans, chunk_reuse=a.chunk_reuse)
     tune_keys = {"bpc": psx.PSX_TUNE_ADAM_BLOCKS_PER_CU, "unroll": psx.PSX_TUNE_ADAM_UNROLL,
                  "nt": psx.PSX_TUNE_NONTEMPORAL, "cbpc": psx.PSX_TUNE_COPY_BLOCKS_PER_CU,
                  "threads": psx.PSX_TUNE_ADAM_THREADS, "wg": psx.PSX_TUNE_ADAM_WG_PER_CU,
@@ -370,7 +373,7 @@ def main():
         "config": {"workload": w.name, "n_elems": n_elems, "n_tensors": len(w.numel), "chunk_elems": w.chunk_elems,
                    "n_chunks": st.nch, "host_resident_chunks": st.n_host, "host_chunks_on_host_cores": st.n_cpu,
                    "loss_scale": w.loss_scale,
-                   "weight_decay": w.weight_decay, "fused_check": not a.separate_check, "skipped_steps": skipped},
+                   "weight_decay": w.weight_decay, "fused_check": not a.separate_check, "chunk_reuse": a.chunk_reuse, "skipped_steps": skipped},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "kernel": "psx::adam_kernel (resident chunks, one launch)",
