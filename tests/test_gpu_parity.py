@@ -396,8 +396,9 @@ def test_host_resident_chunks_stream_through_staging(orc, alias, slots, mode):
 @pytest.mark.parametrize("alias", [False, True])
 def test_skipped_step_still_moves_chunks_that_change_residence(orc, alias, mode):
     """An overflow skips the update, but a chunk admitted to or evicted from HBM in that step must still
-    find its fp32 states, bit for bit, in the new home; aliased fp16 chunks get their parameters back."""
-    ctx = psx.psx_ctx_create(max_chunks=8, max_tensors=4, staging_tile_elems=4096, staging_slots=2)
+    find its fp32 states, bit for bit, in the new home; aliased fp16 chunks get their parameters back.
+    Direct mode needs no staging at all, so its context is created without any."""
+    ctx = psx.psx_ctx_create(max_chunks=8, max_tensors=4, staging_tile_elems=4096 if mode == 0 else 0, staging_slots=2)
     psx.psx_ctx_set_tuning(ctx, psx.PSX_TUNE_HOST_MODE, mode)
     psx.psx_ctx_set_tuning(ctx, psx.PSX_TUNE_HOST_GRID, 5)
     try:
