@@ -243,6 +243,26 @@ typedef struct psx_chunk {
 int32_t psx_chunk_adam_step(psx_ctx *ctx, const psx_chunk *chunks, size_t n_chunks,
                             const psx_adam_hyper *hyper, uint32_t flags, void *stream);
 
+/*
+ * The same step for callers that cannot allocate: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  No context: the overflow flags and the descriptor tables the kernels
+ * search live in one static device array of PSX_NOALLOC_SCRATCH_BYTES that every GPU the library runs on
+ * holds until the process ends, and the descriptors reach it as kernel arguments.  The call issues kernel
+ * launches only: no hipMalloc / hipFree, no memcpy, no memset, nothing that allocates.
+ *   chunks[n_chunks]  host array as above, restricted to loc_in == loc_out == PSX_LOC_HBM and
+ *                     exec == PSX_EXEC_GPU; n_chunks <= PSX_NOALLOC_MAX_CHUNKS, else PSX_ECAP
+ *   flags             0, or PSX_STEP_CHECK_FIRST: test all g16 chunks for inf/nan first and skip the
+ *                     update if one is found (p16 that aliases g16 is then rewritten with fp16(p32))
+ *   flag_out_dev      device, out, may be NULL: receives 0/1 = step skipped (needs PSX_STEP_CHECK_FIRST)
+ * Launch shapes are the library defaults (no tuning knobs).  Asynchronous on `stream`.  Every call on a
+ * GPU uses that GPU's one array and rewrites the parts it needs: calls that overlap in time on one GPU
+ * (two streams, two threads) race; order them.  Arguments are validated before anything is enqueued.
+ */
+#define PSX_NOALLOC_MAX_CHUNKS    1024u
+#define PSX_NOALLOC_SCRATCH_BYTES 262144u
+int32_t psx_chunk_adam_step_noalloc(const psx_chunk *chunks, size_t n_chunks, const psx_adam_hyper *hyper,
+                                    uint32_t flags, uint32_t *flag_out_dev, void *stream);
+
 /* ------------------------------------------------------------------ loss scale
  * Dynamic loss scale bookkeeping on the host (a convention of mixed-precision
  * training; not specified by the paper): an overflow halves the scale (floor 1),

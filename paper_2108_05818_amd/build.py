@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpsx.so")
-SOURCES = ["psx_host.cpp", "psx_cpu.cpp", "psx_kernels.hip", "psx_runtime.hip"]
+SOURCES = ["psx_host.cpp", "psx_cpu.cpp", "psx_kernels.hip", "psx_runtime.hip", "psx_noalloc.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

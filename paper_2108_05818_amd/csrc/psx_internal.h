@@ -61,6 +61,9 @@ struct AdamScalars {
     uint32_t decay_mode;   // 0 none, 1 L2 into the gradient, 2 decoupled
 };
 
+// Validates the hyper-parameters and derives the scalars (`who` names the entry point in messages).
+int32_t prepare_adam_scalars(const psx_adam_hyper *h, const char *who, AdamScalars *s);
+
 struct Tuning {
     int adam_threads = 64;         // 64 or 256 threads per workgroup
     int adam_unroll = 1;           // rows of 4 elements per thread

@@ -588,13 +588,14 @@ extern "C" int32_t psx_overflow_check(psx_ctx *c, const void *const *g16_chunks,
 
 // ====================================================================== Adam step
 
-namespace {
+namespace psx {
 
-int32_t prepare_scalars(const psx_adam_hyper *h, AdamScalars *s) {
-    if (!(h->loss_scale > 0.0) || !std::isfinite(h->loss_scale)) return fail(PSX_EINVAL, "psx_chunk_adam_step: loss_scale must be positive and finite");
-    if (h->step == 0) return fail(PSX_EINVAL, "psx_chunk_adam_step: step is 1-based");
+// Step-wide scalars of the update: derived in double from the caller's doubles, each rounded to fp32 once.
+int32_t prepare_adam_scalars(const psx_adam_hyper *h, const char *who, AdamScalars *s) {
+    if (!(h->loss_scale > 0.0) || !std::isfinite(h->loss_scale)) return fail(PSX_EINVAL, "%s: loss_scale must be positive and finite", who);
+    if (h->step == 0) return fail(PSX_EINVAL, "%s: step is 1-based", who);
     if (!(h->beta1 >= 0.0 && h->beta1 < 1.0) || !(h->beta2 >= 0.0 && h->beta2 < 1.0))
-        return fail(PSX_EINVAL, "psx_chunk_adam_step: betas must lie in [0, 1)");
+        return fail(PSX_EINVAL, "%s: betas must lie in [0, 1)", who);
     const double t = (double)h->step;
     const double b1t = std::pow(h->beta1, t);
     const double b2t = std::pow(h->beta2, t);
@@ -611,6 +612,10 @@ int32_t prepare_scalars(const psx_adam_hyper *h, AdamScalars *s) {
     s->decay_mode = s->wd == 0.0f ? 0u : (h->adamw_mode ? 2u : 1u);
     return PSX_OK;
 }
+
+}  // namespace psx
+
+namespace {
 
 // Resources of the host-core path: worker pool, a stream for the fp16 parameter uploads, pinned
 // staging for fp16 gradient and parameter tiles, events.
@@ -678,7 +683,7 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
     if (n_chunks > c->cfg.max_chunks)
         return fail(PSX_ECAP, "psx_chunk_adam_step: %zu chunks, context holds %llu", n_chunks, (unsigned long long)c->cfg.max_chunks);
     AdamScalars sc;
-    int32_t rc = prepare_scalars(hyper, &sc);
+    int32_t rc = prepare_adam_scalars(hyper, "psx_chunk_adam_step", &sc);
     if (rc != PSX_OK) return rc;
     const bool check_first = (flags & PSX_STEP_CHECK_FIRST) != 0;
     const bool use_flag = check_first || (flags & PSX_STEP_USE_FLAG) != 0;

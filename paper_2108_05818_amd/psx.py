@@ -24,13 +24,14 @@ PSX_TUNE_ADAM_THREADS, PSX_TUNE_ADAM_WG_PER_CU, PSX_TUNE_COPY_UNROLL = 5, 6, 7
 PSX_TUNE_HOST_MODE, PSX_TUNE_HOST_GRID, PSX_TUNE_HOST_UNROLL = 8, 9, 10
 PSX_TUNE_CPU_THREADS, PSX_TUNE_CPU_TILE_ELEMS, PSX_TUNE_CPU_ISA = 11, 12, 13
 PSX_TUNE_COPY_THREADS = 14
+PSX_NOALLOC_MAX_CHUNKS, PSX_NOALLOC_SCRATCH_BYTES = 1024, 262144
 
 EXPORTS = [
     "psx_last_error", "psx_chunk_layout", "psx_ctx_create", "psx_ctx_destroy", "psx_pack", "psx_unpack",
     "psx_overflow_check", "psx_overflow_reset", "psx_overflow_read", "psx_chunk_adam_step",
     "psx_loss_scale_update", "psx_ctx_set_tuning", "psx_ctx_set_profiling", "psx_ctx_get_timing",
     "psx_copy_bytes", "psx_measure_link", "psx_pinned_alloc", "psx_pinned_free", "psx_plan_residency",
-    "psx_chunk_size_search",
+    "psx_chunk_size_search", "psx_chunk_adam_step_noalloc",
 ]
 
 
@@ -103,6 +104,7 @@ def lib():
         "psx_overflow_reset": [vp, vp],
         "psx_overflow_read": [vp, vp, sz, vp, vp],
         "psx_chunk_adam_step": [vp, vp, sz, C.POINTER(psx_adam_hyper), u32, vp],
+        "psx_chunk_adam_step_noalloc": [vp, sz, C.POINTER(psx_adam_hyper), u32, vp, vp],
         "psx_loss_scale_update": [C.POINTER(psx_scaler), u32],
         "psx_ctx_set_tuning": [vp, u32, C.c_int64],
         "psx_ctx_set_profiling": [vp, C.c_int32],
@@ -237,6 +239,11 @@ def make_chunks(specs):
 def psx_chunk_adam_step(ctx, chunks, hyper, flags=0, stream=None, n_chunks=None):
     n = len(chunks) if n_chunks is None else n_chunks
     _ok(lib().psx_chunk_adam_step(ctx, chunks, n, C.byref(hyper), flags, _stream(stream)))
+
+
+def psx_chunk_adam_step_noalloc(chunks, hyper, flags=0, flag_out_dev=None, stream=None, n_chunks=None):
+    n = len(chunks) if n_chunks is None else n_chunks
+    _ok(lib().psx_chunk_adam_step_noalloc(chunks, n, C.byref(hyper), flags, _addr(flag_out_dev), _stream(stream)))
 
 
 def make_scaler(scale=65536.0, growth_interval=2000):

@@ -126,3 +126,21 @@ def test_null_arguments_are_errors_not_crashes():
     assert L.psx_overflow_check(None, None, None, 0, None, None, None) == psx.PSX_EINVAL
     assert L.psx_chunk_adam_step(None, None, 0, None, 0, None) == psx.PSX_EINVAL
     assert b"ctx is NULL" in L.psx_last_error()
+
+
+def test_noalloc_step_validates_before_it_touches_the_gpu():
+    """Size and flag errors of psx_chunk_adam_step_noalloc are found on the host, before any HIP call."""
+    L = psx.lib()
+    h = psx.make_hyper()
+    assert L.psx_chunk_adam_step_noalloc(None, 0, None, 0, None, None) == psx.PSX_EINVAL
+    assert L.psx_chunk_adam_step_noalloc(None, 1, C.byref(h), 0, None, None) == psx.PSX_EINVAL
+    spec = dict(g16=1 << 20, p16=1 << 20, p32=1 << 21, m=1 << 22, v=1 << 23, used=8)
+    many = psx.make_chunks([spec] * (psx.PSX_NOALLOC_MAX_CHUNKS + 1))
+    assert L.psx_chunk_adam_step_noalloc(many, len(many), C.byref(h), 0, None, None) == psx.PSX_ECAP
+    one = psx.make_chunks([spec])
+    assert L.psx_chunk_adam_step_noalloc(one, 1, C.byref(h), psx.PSX_STEP_USE_FLAG, None, None) == psx.PSX_EINVAL
+    assert L.psx_chunk_adam_step_noalloc(one, 1, C.byref(h), 0, 1 << 24, None) == psx.PSX_EINVAL   # flag_out needs the check
+    odd = psx.make_chunks([dict(spec, m=(1 << 22) + 4)])
+    assert L.psx_chunk_adam_step_noalloc(odd, 1, C.byref(h), 0, None, None) == psx.PSX_EALIGN
+    bad = psx.make_hyper(step=0)
+    assert L.psx_chunk_adam_step_noalloc(one, 1, C.byref(bad), 0, None, None) == psx.PSX_EINVAL

@@ -1,0 +1,118 @@
+"""psx_chunk_adam_step_noalloc (the entry point for callers that cannot allocate) against
+psx_chunk_adam_step on identical inputs: every output bit for bit, on calls in a row that share the
+library's one static device array, the later ones with smaller inputs than the earlier ones."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2108_05818_amd import psx
+from paper_2108_05818_amd import workloads as W
+
+from gpu_util import DEV, SENT16, SENT32, bits16, bits32
+
+pytestmark = pytest.mark.gpu
+
+NAMES = ("p32", "m", "v", "p16", "g16")
+
+
+def make_inputs(used, C, seed, alias_every=0, loss_scale=1024.0):
+    """Seeded chunk payloads as numpy arrays (fp16 as bit patterns); padding holds sentinels."""
+    chunks = []
+    for k, u in enumerate(used):
+        c = dict(p32=np.full(C, SENT32, np.uint32).view(np.float32), m=np.full(C, SENT32, np.uint32).view(np.float32),
+                 v=np.full(C, SENT32, np.uint32).view(np.float32), p16=np.full(C, SENT16, np.uint16),
+                 g16=np.full(C, SENT16, np.uint16), alias=bool(alias_every) and k % alias_every == 0)
+        c["p32"][:u] = W.params_np(u, seed + 10 * k)
+        c["m"][:u] = W.params_np(u, seed + 10 * k + 1) * np.float32(0.05)
+        c["v"][:u] = np.abs(W.params_np(u, seed + 10 * k + 2)) * np.float32(1e-4)
+        c["g16"][:u] = W.grads_f16_np(u, seed + 10 * k + 3, loss_scale)
+        chunks.append(c)
+    return chunks
+
+
+def upload(inputs, used):
+    """Device copies of the payloads (each list one arena) and the psx_chunk array over them."""
+    n, C = len(inputs), inputs[0]["p32"].size
+    dev = {}
+    for name in NAMES:
+        dt = torch.float32 if name in ("p32", "m", "v") else torch.int16
+        arena = torch.empty(n * C, dtype=dt, device=DEV)
+        for k, c in enumerate(inputs):
+            src = c[name] if dt == torch.float32 else c[name].view(np.int16)
+            arena[k * C:(k + 1) * C] = torch.from_numpy(src.copy()).to(DEV)
+        dev[name] = [arena[k * C:(k + 1) * C] for k in range(n)]
+    specs = [dict(g16=dev["g16"][k], p16=dev["g16"][k] if inputs[k]["alias"] else dev["p16"][k], p32=dev["p32"][k],
+                  m=dev["m"][k], v=dev["v"][k], used=used[k]) for k in range(n)]
+    return dev, psx.make_chunks(specs)
+
+
+def assert_same(a, b, tag):
+    for name in NAMES:
+        for k, (x, y) in enumerate(zip(a[name], b[name])):
+            assert torch.equal(x.view(torch.int16), y.view(torch.int16)), f"{tag}: chunk {k} {name} differs"
+
+
+def run_pair(ctx, used, C, seed, hp, alias_every=0, plant=None, flags=psx.PSX_STEP_CHECK_FIRST):
+    inputs = make_inputs(used, C, seed, alias_every, hp["loss_scale"])
+    if plant is not None:
+        k, pos, bits = plant
+        inputs[k]["g16"][pos] = bits
+    ref, ref_chunks = upload(inputs, used)
+    got, got_chunks = upload(inputs, used)
+    hyper = psx.make_hyper(**hp)
+    psx.psx_chunk_adam_step(ctx, ref_chunks, hyper, flags)
+    ref_flag = psx.psx_overflow_read(ctx)[0] if flags else 0
+    flag_dev = torch.full((1,), 77, dtype=torch.int32, device=DEV)
+    psx.psx_chunk_adam_step_noalloc(got_chunks, hyper, flags, flag_dev if flags else None)
+    torch.cuda.synchronize()
+    assert_same(got, ref, f"seed {seed}")
+    if flags:
+        assert int(flag_dev.item()) == ref_flag
+    # and the reference really did something / really skipped
+    changed = not torch.equal(ref["p32"][0].view(torch.int32)[:used[0]],
+                              torch.from_numpy(inputs[0]["p32"][:used[0]].view(np.int32).copy()).to(DEV))
+    assert changed == (ref_flag == 0) or used[0] == 0
+    return ref_flag
+
+
+def test_noalloc_matches_the_context_entry_point_on_calls_in_a_row():
+    ctx = psx.psx_ctx_create(max_chunks=128, max_tensors=4)
+    try:
+        C = 20000
+        hp = dict(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01, adamw_mode=0, step=3, loss_scale=1024.0)
+        # 1: 70 chunks (three batches of descriptors), ragged fills around tile boundaries, some reused fp16 chunks
+        rng = np.random.default_rng(5)
+        used70 = [int(x) for x in rng.integers(1, C + 1, size=70)]
+        used70[3], used70[4], used70[5], used70[69] = 0, 256, 257, C
+        assert run_pair(ctx, used70, C, 100, hp, alias_every=3) == 0
+        # 2: a smaller call right after it: 2 chunks, fewer elements, other hyper-parameters
+        hp2 = dict(hp, step=7, weight_decay=0.1, adamw_mode=1, loss_scale=64.0)
+        assert run_pair(ctx, [777, 5], C, 200, hp2) == 0
+        # 3: an inf in the last used element of a reused chunk: both skip, reused chunks get fp16(p32) back
+        assert run_pair(ctx, [4096, 1000, 33], C, 300, hp, alias_every=2, plant=(2, 32, 0x7C00)) == 1
+        # 4: a nan in padding is not an overflow; then a clean larger call again
+        assert run_pair(ctx, [4096, 1000, 33], C, 400, hp, plant=(1, 1000, 0x7E00)) == 0
+        assert run_pair(ctx, used70[:40], C, 500, hp, alias_every=5) == 0
+        # 5: no overflow test at all (flags 0)
+        assert run_pair(ctx, [9000, 123], C, 600, hp, flags=0) == 0
+    finally:
+        psx.psx_ctx_destroy(ctx)
+
+
+def test_noalloc_refuses_what_does_not_fit():
+    z = torch.zeros(64, dtype=torch.float32, device=DEV)
+    h = torch.zeros(64, dtype=torch.float16, device=DEV)
+    spec = dict(g16=h, p16=h, p32=z, m=z, v=z, used=64)
+    too_many = psx.make_chunks([spec] * (psx.PSX_NOALLOC_MAX_CHUNKS + 1))
+    with pytest.raises(psx.PsxError) as e:
+        psx.psx_chunk_adam_step_noalloc(too_many, psx.make_hyper())
+    assert e.value.code == psx.PSX_ECAP and "1025 chunks" in str(e.value)
+    with pytest.raises(psx.PsxError) as e:
+        psx.psx_chunk_adam_step_noalloc(psx.make_chunks([spec]), psx.make_hyper(), psx.PSX_STEP_USE_FLAG)
+    assert e.value.code == psx.PSX_EINVAL
+    host = dict(spec, loc_in=psx.PSX_LOC_HOST, loc_out=psx.PSX_LOC_HOST, p32_host=1 << 20, m_host=1 << 20, v_host=1 << 20)
+    with pytest.raises(psx.PsxError) as e:
+        psx.psx_chunk_adam_step_noalloc(psx.make_chunks([host]), psx.make_hyper())
+    assert e.value.code == psx.PSX_EINVAL
+    torch.cuda.synchronize()
+    assert not z.any() and not h.any()
