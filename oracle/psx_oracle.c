@@ -27,7 +27,9 @@
  * et al. for mixed precision with loss scaling) is written out below in the
  * textbook form; every such reading is listed in the design notes.
  *
- * Pins: see tests/test_oracle_*.py.  The loss-scale growth interval and the
+ * Pins: see tests/test_oracle_*.py (the placement cost at the end of this file:
+ * tests/test_oracle_planner.py with hand-worked cases under tests/golden/).
+ * The loss-scale growth interval and the
  * choice between L2 and decoupled weight decay are conventions, not paper
  * facts: "parity unpinned" for those two (the arithmetic of both decay modes
  * is pinned against a library Adam/AdamW).
@@ -241,7 +243,7 @@ uint32_t orc_overflow_check(const uint16_t *const *g16_chunks, const uint64_t *u
 /*                                                                      */
 /* Hyper-parameters arrive as doubles; step-wide scalars are prepared   */
 /* in double and rounded to fp32 once:                                  */
-/*   b1t = beta1^t, b2t = beta2^t (libm pow), step_size = lr/(1-b1t),  */
+/*   b1t = beta1^t, b2t = beta2^t (t-fold product), step_size = lr/(1-b1t), */
 /*   c2 = 1/sqrt(1-b2t), inv_scale = 1/loss_scale, beta1, beta2,       */
 /*   omb1 = 1-beta1, omb2 = 1-beta2, eps, wd, decay = 1-lr*wd.         */
 /* Per element (each operation rounded to fp32, in this order):        */
@@ -269,8 +271,9 @@ typedef struct {
 
 void orc_adam_prepare(const orc_adam_hyper *h, orc_adam_scalars *s)
 {
-    double b1t = pow(h->beta1, (double)h->step);
-    double b2t = pow(h->beta2, (double)h->step);
+    /* beta^t as its definition: the product of t factors, in double */
+    double b1t = 1.0, b2t = 1.0;
+    for (uint64_t i = 0; i < h->step; i++) { b1t = b1t * h->beta1; b2t = b2t * h->beta2; }
     s->step_size = (float)(h->lr / (1.0 - b1t));
     s->c2 = (float)(1.0 / sqrt(1.0 - b2t));
     s->inv_scale = (float)(1.0 / h->loss_scale);
