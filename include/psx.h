@@ -243,6 +243,12 @@ typedef struct psx_chunk {
 int32_t psx_chunk_adam_step(psx_ctx *ctx, const psx_chunk *chunks, size_t n_chunks,
                             const psx_adam_hyper *hyper, uint32_t flags, void *stream);
 
+/* The step-wide fp32 scalars psx_chunk_adam_step derives from *hyper, in the order step_size, c2,
+ * inv_scale, beta1, beta2, 1-beta1, 1-beta2, eps, weight_decay, decay (see the formulas above); the
+ * same validation as the step call.  out[10], host.  Pure host code: lets a caller (or a test) see
+ * exactly which constants the kernels will use at step t. */
+int32_t psx_adam_step_scalars(const psx_adam_hyper *hyper, float *out);
+
 /*
  * The same step for callers that cannot allocate: code under HIP graph capture, tight serving loops,
  * harnesses that forbid hipMalloc.  No context: the overflow flags and the descriptor tables the kernels

@@ -62,30 +62,18 @@ __device__ __forceinline__ uint32_t find_owner(const uint64_t *__restrict__ begi
 
 // ------------------------------------------------------------------ Adam
 
-// One element of the update, in the operation order of include/psx.h.
+// One element of the update: the formulas of include/psx.h as they stand there.  Contraction is off
+// for this file, so every product, sum, quotient and root below is rounded to fp32 on its own, in
+// the order the parentheses give.  gs is the fp16 gradient converted to fp32 (exact), still scaled.
 template <int DM>
-__device__ __forceinline__ void adam_elem(float g, float &p, float &m, float &v,
+__device__ __forceinline__ void adam_elem(float gs, float &p, float &m, float &v,
                                           const AdamScalars &s) {
-    g = g * s.inv_scale;
-    if constexpr (DM == 1) {
-        float t = s.wd * p;
-        g = g + t;
-    } else if constexpr (DM == 2) {
-        p = p * s.decay;
-    }
-    float a = s.beta1 * m;
-    float b = s.omb1 * g;
-    m = a + b;
-    float c = s.beta2 * v;
-    float d = s.omb2 * g;
-    float e = d * g;
-    v = c + e;
-    float r = __builtin_sqrtf(v);
-    float den = r * s.c2;
-    den = den + s.eps;
-    float q = m / den;
-    float u = s.step_size * q;
-    p = p - u;
+    float g = gs * s.inv_scale;
+    if constexpr (DM == 1) g = g + s.wd * p;             // L2 decay enters through the gradient
+    if constexpr (DM == 2) p = p * s.decay;              // decoupled decay shrinks the parameter first
+    m = s.beta1 * m + s.omb1 * g;
+    v = s.beta2 * v + (s.omb2 * g) * g;
+    p = p - s.step_size * (m / (__builtin_sqrtf(v) * s.c2 + s.eps));
 }
 
 // T threads per workgroup, U rows of 4 elements per thread: a tile is T*4*U

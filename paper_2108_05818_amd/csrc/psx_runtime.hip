@@ -615,6 +615,16 @@ int32_t prepare_adam_scalars(const psx_adam_hyper *h, const char *who, AdamScala
 
 }  // namespace psx
 
+extern "C" int32_t psx_adam_step_scalars(const psx_adam_hyper *hyper, float *out) {
+    if (hyper == nullptr || out == nullptr) return fail(PSX_EINVAL, "psx_adam_step_scalars: NULL argument");
+    AdamScalars s;
+    const int32_t rc = prepare_adam_scalars(hyper, "psx_adam_step_scalars", &s);
+    if (rc != PSX_OK) return rc;
+    const float v[10] = {s.step_size, s.c2, s.inv_scale, s.beta1, s.beta2, s.omb1, s.omb2, s.eps, s.wd, s.decay};
+    memcpy(out, v, sizeof(v));
+    return PSX_OK;
+}
+
 namespace {
 
 // Resources of the host-core path: worker pool, a stream for the fp16 parameter uploads, pinned

@@ -31,7 +31,7 @@ EXPORTS = [
     "psx_overflow_check", "psx_overflow_reset", "psx_overflow_read", "psx_chunk_adam_step",
     "psx_loss_scale_update", "psx_ctx_set_tuning", "psx_ctx_set_profiling", "psx_ctx_get_timing",
     "psx_copy_bytes", "psx_measure_link", "psx_pinned_alloc", "psx_pinned_free", "psx_plan_residency",
-    "psx_chunk_size_search", "psx_chunk_adam_step_noalloc",
+    "psx_chunk_size_search", "psx_chunk_adam_step_noalloc", "psx_adam_step_scalars",
 ]
 
 
@@ -105,6 +105,7 @@ def lib():
         "psx_overflow_read": [vp, vp, sz, vp, vp],
         "psx_chunk_adam_step": [vp, vp, sz, C.POINTER(psx_adam_hyper), u32, vp],
         "psx_chunk_adam_step_noalloc": [vp, sz, C.POINTER(psx_adam_hyper), u32, vp, vp],
+        "psx_adam_step_scalars": [C.POINTER(psx_adam_hyper), vp],
         "psx_loss_scale_update": [C.POINTER(psx_scaler), u32],
         "psx_ctx_set_tuning": [vp, u32, C.c_int64],
         "psx_ctx_set_profiling": [vp, C.c_int32],
@@ -244,6 +245,16 @@ def psx_chunk_adam_step(ctx, chunks, hyper, flags=0, stream=None, n_chunks=None)
 def psx_chunk_adam_step_noalloc(chunks, hyper, flags=0, flag_out_dev=None, stream=None, n_chunks=None):
     n = len(chunks) if n_chunks is None else n_chunks
     _ok(lib().psx_chunk_adam_step_noalloc(chunks, n, C.byref(hyper), flags, _addr(flag_out_dev), _stream(stream)))
+
+
+SCALAR_NAMES = ("step_size", "c2", "inv_scale", "beta1", "beta2", "omb1", "omb2", "eps", "wd", "decay")
+
+
+def psx_adam_step_scalars(hyper):
+    """-> dict of the ten fp32 scalars (as Python floats holding exact fp32 values)."""
+    out = (C.c_float * 10)()
+    _ok(lib().psx_adam_step_scalars(C.byref(hyper), out))
+    return dict(zip(SCALAR_NAMES, out))
 
 
 def make_scaler(scale=65536.0, growth_interval=2000):

@@ -144,3 +144,24 @@ def test_noalloc_step_validates_before_it_touches_the_gpu():
     assert L.psx_chunk_adam_step_noalloc(odd, 1, C.byref(h), 0, None, None) == psx.PSX_EALIGN
     bad = psx.make_hyper(step=0)
     assert L.psx_chunk_adam_step_noalloc(one, 1, C.byref(bad), 0, None, None) == psx.PSX_EINVAL
+
+
+def test_step_scalars_agree_with_the_oracle_over_many_steps(orc):
+    """The library derives beta^t with libm pow, the oracle as the t-fold product: two derivations that
+    share nothing.  After rounding to fp32 all ten scalars must be the same numbers at every step the
+    tests and benchmarks can reach (every t up to 20000, then every 97th up to 10^5), for several betas."""
+    cases = [dict(lr=1e-3, beta1=0.9, beta2=0.999, weight_decay=0.01, loss_scale=65536.0),
+             dict(lr=3e-4, beta1=0.95, beta2=0.98, weight_decay=0.1, adamw_mode=1, loss_scale=1024.0),
+             dict(lr=1e-2, beta1=0.8, beta2=0.9999, eps=1e-6, loss_scale=1.0),
+             dict(lr=5e-4, beta1=0.0, beta2=0.5, loss_scale=3.0)]
+    for i, hp in enumerate(cases):
+        steps = list(range(1, 20001 if i == 0 else 2001)) + list(range(20001, 100001, 97 if i == 0 else 4999))
+        for t in steps:
+            mine = psx.psx_adam_step_scalars(psx.make_hyper(step=t, **hp))
+            ref = orc.adam_prepare(orc.hyper(step=t, **hp))
+            for name in psx.SCALAR_NAMES:
+                assert mine[name] == getattr(ref, name), (hp, t, name)
+    with pytest.raises(psx.PsxError):
+        psx.psx_adam_step_scalars(psx.make_hyper(step=0))
+    with pytest.raises(psx.PsxError):
+        psx.psx_adam_step_scalars(psx.make_hyper(beta2=1.0))

@@ -11,7 +11,7 @@ import oracle
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 PIN_FILES = ["tests/test_oracle_fp16.py", "tests/test_oracle_layout.py", "tests/test_oracle_pack_overflow.py",
-             "tests/test_oracle_adam.py"]
+             "tests/test_oracle_adam.py", "tests/test_oracle_planner.py"]
 
 MUTANTS = [
     ("momentum sign", "m = a + b;", "m = a - b;"),
@@ -40,6 +40,28 @@ MUTANTS = [
     ("skipped step leaves grads in the reused chunk", "else if (g16[c] == p16[c])", "else if (0)"),
     ("pack writes one element late", "+ (lin % chunk_elems) * elem_size;\n            for (uint64_t b = 0; b < elem_size; b++) dst[b]",
      "+ ((lin + 1) % chunk_elems) * elem_size;\n            for (uint64_t b = 0; b < elem_size; b++) dst[b]"),
+    ("unpack reads one element late", "+ (lin % chunk_elems) * elem_size;\n            for (uint64_t b = 0; b < elem_size; b++) dst[k * elem_size + b]",
+     "+ ((lin + 1) % chunk_elems) * elem_size;\n            for (uint64_t b = 0; b < elem_size; b++) dst[k * elem_size + b]"),
+    ("re-cast misses the last element", "for (uint64_t k = 0; k < used; k++) p16[k] = orc_f32_to_f16(p32[k]);",
+     "for (uint64_t k = 0; k + 1 < used; k++) p16[k] = orc_f32_to_f16(p32[k]);"),
+    ("re-cast truncates instead of rounding", "for (uint64_t k = 0; k < used; k++) p16[k] = orc_f32_to_f16(p32[k]);",
+     "for (uint64_t k = 0; k < used; k++) { uint32_t x; memcpy(&x, &p32[k], 4); x &= 0xFFFFE000u; float f; memcpy(&f, &x, 4); p16[k] = orc_f32_to_f16(f); }"),
+    ("bias correction of v without the root", "s->c2 = (float)(1.0 / sqrt(1.0 - b2t));", "s->c2 = (float)(1.0 / (1.0 - b2t));"),
+    ("unscale multiplies by the loss scale", "s->inv_scale = (float)(1.0 / h->loss_scale);", "s->inv_scale = (float)(h->loss_scale);"),
+    ("beta^t with one factor too few", "for (uint64_t i = 0; i < h->step; i++) { b1t", "for (uint64_t i = 1; i < h->step; i++) { b1t"),
+    ("decoupled decay factor without lr", "s->decay = (float)(1.0 - h->lr * h->weight_decay);", "s->decay = (float)(1.0 - h->weight_decay);"),
+    ("scaler: t advances on an overflow step", "        s->scale = half < 1.0f ? 1.0f : half;\n        s->good_steps = 0;",
+     "        s->scale = half < 1.0f ? 1.0f : half;\n        s->good_steps = 0; s->step += 1;"),
+    ("scaler: scale doubles on overflow", "float half = s->scale * 0.5f;", "float half = s->scale * 2.0f;"),
+    ("scaler: no floor at 1", "s->scale = half < 1.0f ? 1.0f : half;", "s->scale = half;"),
+    ("scaler: good steps not reset on overflow", "        s->scale = half < 1.0f ? 1.0f : half;\n        s->good_steps = 0;",
+     "        s->scale = half < 1.0f ? 1.0f : half;"),
+    ("placement: only the inbound direction is charged", "if (!after) cost += 12 * used[k];", "if (0) cost += 12 * used[k];"),
+    ("placement: only the outbound direction is charged", "if (!before) cost += 12 * used[k];", "if (0) cost += 12 * used[k];"),
+    ("placement: budget tested on the state before the step", "resident += (uint64_t)after;", "resident += (uint64_t)before;"),
+    ("placement: 4 bytes per element instead of 12", "if (!before) cost += 12 * used[k];", "if (!before) cost += 4 * used[k];"),
+    ("placement: first step takes everything as resident", "int before = t == 0 ? start[k] :", "int before = t == 0 ? 1 :"),
+    ("placement: budget may be exceeded by one", "if (resident > budget[t]) ok = 0;", "if (resident > budget[t] + 1) ok = 0;"),
 ]
 
 
