@@ -43,7 +43,16 @@ def parse():
     ap.add_argument("--chunk-reuse", action="store_true",
                     help="the paper's chunk reuse: gradients are packed into the fp16 parameter chunks and overwritten "
                          "there by the new parameters (default: a gradient chunk list of its own)")
+    ap.add_argument("--arena-skew", type=int, default=0, metavar="BYTES",
+                    help="start chunk list j of the device arenas j*BYTES into its allocation (multiple of 256): "
+                         "moves the streams of one chunk relative to each other in the address space")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep-wg", default="", metavar="LIST",
+                    help="after the timed steps, time the Adam launch with each of these caps on resident workgroups "
+                         "per CU (comma list, 0 = no cap), all in the same allocation")
+    ap.add_argument("--no-legs", action="store_true",
+                    help="default run only: skip the extra legs (chunk reuse on the same workload; GPT-12.6B with "
+                         "40 %% of the chunks host-resident, over the link and on the host cores)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="also launch psx_copy_bytes once over this many MiB (a plain copy of known size, "
                          "the yardstick the HBM traffic counters are scaled by)")
@@ -59,7 +68,7 @@ class State:
 
 
 def setup(w, dev, host_fraction=0.0, staging_tile_elems=4 << 20, staging_slots=3, keep_params="all", cpu_share=0.0,
-          plans=None, chunk_reuse=False):
+          plans=None, chunk_reuse=False, arena_skew=0):
     """Allocate chunk lists and seeded inputs on the device (and pinned host memory for
     host-resident chunks); pack the fp32 params tensor by tensor; m = v = 0.
     keep_params: "all" keeps every fp32 source tensor, an int keeps only the first that many, a set keeps
@@ -92,12 +101,17 @@ def setup(w, dev, host_fraction=0.0, staging_tile_elems=4 << 20, staging_slots=3
                                 staging_tile_elems=staging_tile_elems if n_host else 0, staging_slots=staging_slots)
     C = st.C
 
+    lists_made = [0]
+
     def chunk_list(dtype, n):
         """One chunk list = one arena, chunk k at offset k*C (the paper's ChunkLists: a list of chunks per
         tensor type).  Besides being the natural layout it keeps the five streams of a chunk apart in
         memory: p/m/v buffers of one chunk allocated back to back sit at power-of-two distances from each
         other, which costs up to 13 % of the Adam kernel's bandwidth with small chunks."""
-        arena = torch.zeros(C * max(n, 1), dtype=dtype, device=dev)
+        item = torch.empty(0, dtype=dtype).element_size()
+        skew = lists_made[0] * arena_skew // item            # elements; list j starts j*arena_skew bytes into its arena
+        lists_made[0] += 1
+        arena = torch.zeros(C * max(n, 1) + skew, dtype=dtype, device=dev)[skew:]
         return [arena[k * C:(k + 1) * C] for k in range(n)]
     st.p16 = chunk_list(torch.float16, st.nch)
     st.g16 = st.p16 if chunk_reuse else chunk_list(torch.float16, st.nch)
@@ -189,51 +203,71 @@ def run_step(st, fused_check=False, new_loc=None):
 
 def cpu_baseline(st, target_chunks=16):
     """The oracle, as it stands, on the host cores: one whole step (gradient pack, overflow check,
-    Adam, fp16 unpack) over the first tensors of the workload that fill `target_chunks` chunks.
-    Tensors and chunks are spread over threads; the oracle's own code is single-threaded C."""
+    Adam, fp16 unpack) over the first tensors of the workload that fill `target_chunks` chunks, with
+    tensors and chunks spread over threads (the oracle's own code is single-threaded C); then the same
+    step on one thread over the first tensors that fill at least one chunk (the parity reference as
+    the tests run it)."""
     import numpy as np
+    import torch
     import oracle as orc
 
     w, C = st.w, st.C
-    # prefix of the tensor list that ends on or before the end of chunk target_chunks-1
     o_slots, o_used = orc.chunk_layout(w.numel, C)
-    T = 0
-    for i in range(min(len(w.numel), CPU_BASELINE_TENSORS)):
-        end = o_slots[i].chunk * C + o_slots[i].offset + o_slots[i].numel
-        if end > target_chunks * C:
-            break
-        T = i + 1
-    if T == 0:
-        T = 1
-    numel = w.numel[:T]
-    slots, used = orc.chunk_layout(numel, C)
-    nch = len(used)
-    n_elems = int(sum(numel))
-    threads = max(1, min(16, len(os.sched_getaffinity(0)), max(nch, 1)))
-    g_np = [st.g_t[i].view(__import__("torch").int16).cpu().numpy().view(np.uint16) for i in range(T)]
-    p_np = [st.p_t[i].cpu().numpy() for i in range(T)]
-    ch = dict(p32=[np.zeros(C, np.float32) for _ in range(nch)], m=[np.zeros(C, np.float32) for _ in range(nch)],
-              v=[np.zeros(C, np.float32) for _ in range(nch)], p16=[np.zeros(C, np.uint16) for _ in range(nch)],
-              g16=[np.zeros(C, np.uint16) for _ in range(nch)])
-    out = [np.zeros(s, np.uint16) for s in numel]
-    sub = lambda i: (orc.Slot * 1)(slots[i])
-    pool = ThreadPoolExecutor(threads)
-    list(pool.map(lambda i: orc.pack([p_np[i]], sub(i), ch["p32"], C), range(T)))          # untimed set-up
-    h = orc.hyper(lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps, weight_decay=w.weight_decay,
-                  adamw_mode=w.adamw_mode, step=1, loss_scale=w.loss_scale)
-    t0 = time.perf_counter()
-    orc.chunk_layout(numel, C)
-    list(pool.map(lambda i: orc.pack([g_np[i]], sub(i), ch["g16"], C), range(T)))
-    flags = list(pool.map(lambda k: orc.overflow_check([ch["g16"][k]], [used[k]])[0], range(nch)))
-    if not any(flags):
-        list(pool.map(lambda k: orc.adam_chunk(ch["g16"][k], ch["p16"][k], ch["p32"][k], ch["m"][k], ch["v"][k],
-                                               int(used[k]), h), range(nch)))
-    list(pool.map(lambda i: orc.unpack([out[i]], sub(i), ch["p16"], C), range(T)))
-    dt = time.perf_counter() - t0
-    pool.shutdown()
+
+    def prefix(chunks_wanted, at_least_one_chunk=False):
+        """Tensors 0..T-1: the longest prefix that ends inside the first `chunks_wanted` chunks
+        (or, with at_least_one_chunk, the shortest one that fills a whole chunk)."""
+        T = 0
+        for i in range(min(len(w.numel), CPU_BASELINE_TENSORS)):
+            end = o_slots[i].chunk * C + o_slots[i].offset + o_slots[i].numel
+            if at_least_one_chunk:
+                T = i + 1
+                if end >= C:
+                    break
+            else:
+                if end > chunks_wanted * C:
+                    break
+                T = i + 1
+        return max(T, 1)
+
+    def one_step(T, threads):
+        numel = w.numel[:T]
+        slots, used = orc.chunk_layout(numel, C)
+        nch = len(used)
+        n_elems = int(sum(numel))
+        threads = max(1, min(threads, max(nch, 1)))
+        g_np = [st.g_t[i].view(torch.int16).cpu().numpy().view(np.uint16) for i in range(T)]
+        p_np = [st.p_t[i].cpu().numpy() for i in range(T)]
+        ch = dict(p32=[np.zeros(C, np.float32) for _ in range(nch)], m=[np.zeros(C, np.float32) for _ in range(nch)],
+                  v=[np.zeros(C, np.float32) for _ in range(nch)], p16=[np.zeros(C, np.uint16) for _ in range(nch)],
+                  g16=[np.zeros(C, np.uint16) for _ in range(nch)])
+        out = [np.zeros(s, np.uint16) for s in numel]
+        sub = lambda i: (orc.Slot * 1)(slots[i])
+        pool = ThreadPoolExecutor(threads)
+        list(pool.map(lambda i: orc.pack([p_np[i]], sub(i), ch["p32"], C), range(T)))          # untimed set-up
+        h = orc.hyper(lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps, weight_decay=w.weight_decay,
+                      adamw_mode=w.adamw_mode, step=1, loss_scale=w.loss_scale)
+        t0 = time.perf_counter()
+        orc.chunk_layout(numel, C)
+        list(pool.map(lambda i: orc.pack([g_np[i]], sub(i), ch["g16"], C), range(T)))
+        flags = list(pool.map(lambda k: orc.overflow_check([ch["g16"][k]], [used[k]])[0], range(nch)))
+        if not any(flags):
+            list(pool.map(lambda k: orc.adam_chunk(ch["g16"][k], ch["p16"][k], ch["p32"][k], ch["m"][k], ch["v"][k],
+                                                   int(used[k]), h), range(nch)))
+        list(pool.map(lambda i: orc.unpack([out[i]], sub(i), ch["p16"], C), range(T)))
+        dt = time.perf_counter() - t0
+        pool.shutdown()
+        return n_elems, nch, threads, dt, T
+
+    cores = max(1, min(16, len(os.sched_getaffinity(0))))
+    n_elems, nch, threads, dt, T = one_step(prefix(target_chunks), cores)
+    n1, nch1, _, dt1, T1 = one_step(prefix(1, at_least_one_chunk=True), 1)
     return {"value": n_elems / dt / 1e9, "unit": "Gelem/s", "cores": threads, "kind": "oracle",
             "sample": f"one whole step on the first {T} tensors ({n_elems} elements, {nch} chunks of {C}) "
-                      f"of the same workload, {dt:.2f} s wall on {threads} threads"}
+                      f"of the same workload, {dt:.2f} s wall on {threads} threads",
+            "single_thread": {"value": n1 / dt1 / 1e9, "unit": "Gelem/s", "cores": 1,
+                              "sample": f"the same step on the first {T1} tensor(s) ({n1} elements, {nch1} chunks of {C}), "
+                                        f"{dt1:.2f} s wall on one thread"}}
 
 
 def read_traffic(path):
@@ -248,34 +282,29 @@ def read_traffic(path):
     return None
 
 
-def main():
-    a = parse()
-    if a.gpus != 1:
-        print("bench.py measures one GPU: this path has no collectives and is not sharded here; "
-              "run with --gpus 1 (total throughput of N GPUs is N independent copies of this number).",
-              file=sys.stderr)
-        sys.exit(2)
-    import torch
+def pick_workload(a):
+    """-> (workload, host_fraction, plans, scaled_from)."""
     from paper_2108_05818_amd import psx
     from paper_2108_05818_amd import workloads as W
-
-    if not os.path.exists(psx.LIB_PATH):
-        import __graft_entry__
-        __graft_entry__.build()
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    torch.cuda.set_device(0)
-    dev = "cuda:0"
+    scaled_from = None
     if a.workload == "tiny":
         w = W.config1_tiny()
     elif a.workload == "ragged":
         w = W.config3_ragged()
     elif a.workload == "gpt12b":
         w = W.config4_gpt12b(a.layers or 40)
+        if w.name != W.config4_gpt12b().name:
+            scaled_from = f"{W.config4_gpt12b().name}: layer count only; hidden size, vocabulary and chunk size kept"
     elif a.workload == "gpt20b":
         # 44 layers need 170 GB of pinned memory; 12 layers of the same tensors fit this box's limit
         w = W.config5_gpt20b(a.layers or 12)
+        if w.name != W.config5_gpt20b().name:
+            scaled_from = (f"{W.config5_gpt20b().name} (401 chunks, about 170 GB of pinned host state; the box pins at most "
+                           "65 GiB): layer count only; hidden size, vocabulary and chunk size kept")
     else:
         w = W.config2_gpt1b(a.layers or 20)
+        if w.name != W.config2_gpt1b().name:
+            scaled_from = f"{W.config2_gpt1b().name}: layer count only"
     if a.chunk_elems:
         w.chunk_elems = a.chunk_elems
         w.name += f"-C{a.chunk_elems}"
@@ -289,10 +318,212 @@ def main():
         per_chunk = 12 * w.chunk_elems
         budget = lambda t: int(round(len(used) * W.budget_fraction(t, 1.0 - host_fraction, w.budget_jitter, w.seed))) * per_chunk
         plans = [psx.psx_plan_residency(used, w.chunk_elems, budget(t))[0] for t in range(a.warmup + a.steps + 1)]
+    return w, host_fraction, plans, scaled_from
+
+
+def timed_steps(st, steps, warmup, fused_check, plans=None):
+    """`warmup` untimed steps, then exactly `steps` timed ones between two device synchronisations.
+    Returns wall ms per step, the per-launch HIP-event times averaged over the timed steps, the link
+    bytes summed over them, and the last step's psx_timing."""
+    import torch
+    from paper_2108_05818_amd import psx
+    psx.psx_ctx_set_profiling(st.ctx, 1)
+    plan_at = (lambda t: plans[t]) if plans else (lambda t: None)
+    for i in range(warmup):
+        run_step(st, fused_check, plan_at(1 + i))
+    torch.cuda.synchronize()
+    phase = {"pack_ms": 0.0, "check_ms": 0.0, "adam_ms": 0.0, "spill_ms": 0.0}
+    link = {"h2d": 0, "d2h": 0, "min_h2d": 0, "min_d2h": 0, "moved_chunks": 0, "resident_chunks": []}
+    skipped = 0
+    tm = None
+    t0 = time.perf_counter()
+    for i in range(steps):
+        before = list(st.loc)
+        skipped += run_step(st, fused_check, plan_at(1 + warmup + i))
+        tm = psx.psx_ctx_get_timing(st.ctx)      # events of this step; the stream is already drained
+        phase["pack_ms"] += tm.pack_ms; phase["check_ms"] += tm.check_ms
+        phase["adam_ms"] += tm.adam_ms; phase["spill_ms"] += tm.spill_ms
+        # every chunk that starts the step on the host must come in once, every chunk that ends it there
+        # must go out once: 12 bytes per used element each
+        link["h2d"] += int(tm.h2d_bytes); link["d2h"] += int(tm.d2h_bytes)
+        link["min_h2d"] += 12 * sum(u for u, l, s in zip(st.used, before, st.specs) if l == psx.PSX_LOC_HOST and s.get("exec", 0) == psx.PSX_EXEC_GPU)
+        link["min_d2h"] += 12 * sum(u for u, l, s in zip(st.used, st.loc, st.specs) if l == psx.PSX_LOC_HOST and s.get("exec", 0) == psx.PSX_EXEC_GPU)
+        link["moved_chunks"] += sum(x != y for x, y in zip(before, st.loc))
+        link["resident_chunks"].append(sum(l == psx.PSX_LOC_HBM for l in st.loc))
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    sums = dict(phase)
+    for k in phase:
+        phase[k] /= max(steps, 1)
+    return {"ms": dt * 1e3 / max(steps, 1), "phase": phase, "phase_sum_ms": sums, "link": link, "tm": tm, "skipped": skipped}
+
+
+def plain_copy_rate(ctx, dev):
+    """A same-run yardstick for the roofline: this library's plain copy kernel over 1 GiB (1 read + 1 write stream)."""
+    import torch
+    from paper_2108_05818_amd import psx
+    nb = 1 << 30
+    src = torch.ones(nb // 4, dtype=torch.float32, device=dev)
+    dst = torch.zeros_like(src)
+    for _ in range(3):
+        psx.psx_copy_bytes(ctx, dst, src, nb)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(10):
+        psx.psx_copy_bytes(ctx, dst, src, nb)         # launched on torch's current stream, as the events are
+    e1.record()
+    torch.cuda.synchronize()
+    return 10 * 2 * nb / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+
+def adam_roofline(r, copy_gbs=None):
+    """HBM roofline of the resident Adam launch from the HIP-event times of `timed_steps`."""
+    adam_elems = int(r["tm"].adam_elems)
+    adam_bytes = ADAM_BYTES_PER_ELEM * adam_elems
+    ms = r["phase"]["adam_ms"]
+    achieved = adam_bytes / (ms * 1e-3) / 1e9 if ms > 0 else 0.0
+    out = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+           "kernel": "psx::adam_kernel (resident chunks, one launch)", "bytes_per_launch": adam_bytes, "avg_launch_ms": ms}
+    if copy_gbs:
+        out.update(same_run_plain_copy_GBs=copy_gbs, frac_of_plain_copy=achieved / copy_gbs)
+    return out
+
+
+def host_link_report(st, r, mode):
+    """Achieved link rates of the host-resident part over the timed steps (bytes and span times summed
+    over all of them), next to both same-run pinned-copy rates of this machine."""
+    from paper_2108_05818_amd import psx
+    tm, link = r["tm"], r["link"]
+    link_s = r["phase_sum_ms"]["spill_ms"] * 1e-3
+    rates = psx.psx_measure_link(st.ctx, 1024, 5)      # same copy streams as the staged pipeline, pinned memory
+    peak = {"copy_h2d_alone_GBs": rates.h2d_alone, "copy_d2h_alone_GBs": rates.d2h_alone,
+            "copy_each_way_both_at_once_GBs": rates.each_way_both, "copy_MiB": 1024}
+    h2d = link["h2d"] / link_s / 1e9 if link_s and link["h2d"] else None
+    d2h = link["d2h"] / link_s / 1e9 if link_s and link["d2h"] else None
+    each = min(x for x in (h2d, d2h) if x) if (h2d or d2h) else None
+    steps = max(len(link["resident_chunks"]), 1)
+    return {"bound": "host link, 12 B/element each way, both directions at once",
+            "mode": {1: "direct (the kernel reads and writes pinned memory over the link)", 0: "staged (H2D, kernel, D2H on copy streams)"}[mode],
+            "h2d_GBs": h2d, "d2h_GBs": d2h, "measured_peak": peak,
+            # two denominators: the best pinned-copy rate of one direction alone, and what hipMemcpyAsync
+            # reaches per direction with both directions busy (less, with this runtime)
+            "frac": each / max(rates.h2d_alone, rates.d2h_alone) if each else None,
+            "frac_of_copies_both_at_once": each / rates.each_way_both if each else None,
+            "host_cores": {"elems": int(tm.cpu_elems), "threads": int(tm.cpu_threads), "ms": float(tm.cpu_ms),
+                           "gelem_s": tm.cpu_elems / (tm.cpu_ms * 1e-3) / 1e9 if tm.cpu_ms else None},
+            "host_part_gelem_s": (tm.spill_elems + tm.cpu_elems) * steps / link_s / 1e9 if link_s else None,
+            "spill_elems": int(tm.spill_elems), "spill_ms": r["phase"]["spill_ms"],
+            "link_bytes": link["h2d"] + link["d2h"], "link_bytes_minimum": link["min_h2d"] + link["min_d2h"]}
+
+
+def release(st):
+    import gc
+    import torch
+    from paper_2108_05818_amd import psx
+    psx.psx_ctx_destroy(st.ctx)
+    for hs in st.host:
+        for b in hs or []:
+            b.free()
+    st.__dict__.clear()
+    gc.collect()
+    torch.cuda.empty_cache()
+
+
+def leg_chunk_reuse(st):
+    """The paper's layout (Sec. "Preprocessing Stage": the gradient sits in the param fp16 chunk) on the
+    headline workload and on the headline's own buffers: the gradient list is dropped and gradients are
+    packed into the fp16 parameter chunks, so the Adam launch reads gradients from, and writes parameters
+    to, the same fp16 chunk.  Same p32/m/v/p16 memory as the headline: only the aliasing differs."""
+    from paper_2108_05818_amd import psx
+    w = st.w
+    for k, s in enumerate(st.specs):
+        s["g16"] = st.p16[k]
+    st.g16 = st.p16
+    st.chunks = psx.make_chunks(st.specs)
+    r = timed_steps(st, 10, 3, True)
+    return {"workload": w.name, "steps": 10, "warmup": 3, "ms_per_step": r["ms"], "gelem_s": w.n_elems / (r["ms"] * 1e-3) / 1e9,
+            "bytes_of_chunk_lists_per_param": 14, "roofline": adam_roofline(r)}
+
+
+def sweep_wg(st, values):
+    """Adam launch time against the cap on resident workgroups per CU, in one allocation (so the
+    placement of the buffers in memory is the same for every value)."""
+    from paper_2108_05818_amd import psx
+    out = {}
+    for wg in values:
+        psx.psx_ctx_set_tuning(st.ctx, psx.PSX_TUNE_ADAM_WG_PER_CU, wg)
+        r = timed_steps(st, 3, 1, True)
+        out[str(wg)] = {"adam_ms": r["phase"]["adam_ms"], "frac": adam_roofline(r)["frac"]}
+    psx.psx_ctx_set_tuning(st.ctx, psx.PSX_TUNE_ADAM_WG_PER_CU, 14)
+    return out
+
+
+def leg_host(a, dev):
+    """Config 4 at full size (GPT-12.6B, 244 chunks of 64 Mi, the last 40 % host-resident), first with the
+    GPU updating the host-resident chunks over the link (the benchmark spec's spilled case), then with the host
+    cores updating them (the paper's own placement for host-resident optimizer states)."""
+    from paper_2108_05818_amd import psx
+    from paper_2108_05818_amd import workloads as W
+    w = W.config4_gpt12b()
+    st = setup(w, dev, w.host_fraction, a.staging_tile, a.staging_slots, keep_params=0)
+    mode = 1
+    r = timed_steps(st, 5, 2, True)
+    link = {"workload": w.name, "n_elems": w.n_elems, "n_chunks": st.nch, "host_resident_chunks": st.n_host,
+            "steps": 5, "warmup": 2, "ms_per_step": r["ms"], "gelem_s": w.n_elems / (r["ms"] * 1e-3) / 1e9,
+            "resident_adam_ms": r["phase"]["adam_ms"]}
+    link.update(host_link_report(st, r, mode))
+    cores = None
+    if psx_cpu_ok():
+        for s in st.specs:
+            if s.get("loc_in") == psx.PSX_LOC_HOST:
+                s["exec"] = psx.PSX_EXEC_CPU
+        st.chunks = psx.make_chunks(st.specs)
+        r = timed_steps(st, 3, 1, True)
+        tm = r["tm"]
+        cores = {"workload": w.name, "steps": 3, "warmup": 1, "ms_per_step": r["ms"], "gelem_s": w.n_elems / (r["ms"] * 1e-3) / 1e9,
+                 "host_elems": int(tm.cpu_elems), "threads": int(tm.cpu_threads), "host_update_ms": float(tm.cpu_ms),
+                 "host_gelem_s": tm.cpu_elems / (tm.cpu_ms * 1e-3) / 1e9 if tm.cpu_ms else None,
+                 "host_dram_GBs": ADAM_BYTES_PER_ELEM * tm.cpu_elems / (tm.cpu_ms * 1e-3) / 1e9 if tm.cpu_ms else None,
+                 "link_bytes_per_elem": 4, "resident_adam_ms": r["phase"]["adam_ms"]}
+    release(st)
+    return link, cores
+
+
+def psx_cpu_ok():
+    """PSX_EXEC_CPU needs AVX2 + F16C on the host."""
+    try:
+        flags = open("/proc/cpuinfo").read()
+        return " avx2" in flags and " f16c" in flags
+    except OSError:
+        return False
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py measures one GPU: this path has no collectives and is not sharded here; "
+              "run with --gpus 1 (total throughput of N GPUs is N independent copies of this number).",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2108_05818_amd import psx
+
+    if not os.path.exists(psx.LIB_PATH):
+        import __graft_entry__
+        __graft_entry__.build()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = "cuda:0"
+    w, host_fraction, plans, scaled_from = pick_workload(a)
+    # the default run (headline workload, no overrides) appends the other halves of the metric as legs
+    headline = (a.workload == "gpt1b" and not a.layers and not a.chunk_elems and host_fraction == 0
+                and not a.chunk_reuse and not a.tune and not a.arena_skew)
+    legs = headline and not a.no_legs
     # the fp32 source tensors are needed again only by the oracle leg, and only the first few of them
     st = setup(w, dev, host_fraction, a.staging_tile, a.staging_slots,
                keep_params=0 if a.no_cpu_baseline else CPU_BASELINE_TENSORS,
-               cpu_share=0.0 if plans else a.cpu_share, plans=plans, chunk_reuse=a.chunk_reuse)
+               cpu_share=0.0 if plans else a.cpu_share, plans=plans, chunk_reuse=a.chunk_reuse,
+               arena_skew=a.arena_skew)
     tune_keys = {"bpc": psx.PSX_TUNE_ADAM_BLOCKS_PER_CU, "unroll": psx.PSX_TUNE_ADAM_UNROLL,
                  "nt": psx.PSX_TUNE_NONTEMPORAL, "cbpc": psx.PSX_TUNE_COPY_BLOCKS_PER_CU,
                  "threads": psx.PSX_TUNE_ADAM_THREADS, "wg": psx.PSX_TUNE_ADAM_WG_PER_CU,
@@ -300,9 +531,12 @@ def main():
                  "hostgrid": psx.PSX_TUNE_HOST_GRID, "hostunroll": psx.PSX_TUNE_HOST_UNROLL,
                  "cputhreads": psx.PSX_TUNE_CPU_THREADS, "cputile": psx.PSX_TUNE_CPU_TILE_ELEMS,
                  "cpuisa": psx.PSX_TUNE_CPU_ISA, "cthreads": psx.PSX_TUNE_COPY_THREADS}
+    host_mode = 1
     for kv in filter(None, a.tune.split(",")):
         k, v = kv.split("=")
         psx.psx_ctx_set_tuning(st.ctx, tune_keys[k], int(v))
+        if k == "hostmode":
+            host_mode = int(v)
 
     if a.copy_calibration:
         nb = a.copy_calibration << 20
@@ -315,54 +549,16 @@ def main():
     if not a.no_cpu_baseline:
         cpu = cpu_baseline(st)
 
-    psx.psx_ctx_set_profiling(st.ctx, 1)
-    plan_at = (lambda t: plans[t]) if plans else (lambda t: None)
-    for i in range(a.warmup):
-        run_step(st, not a.separate_check, plan_at(1 + i))
-    torch.cuda.synchronize()
-    phase = {"pack_ms": 0.0, "check_ms": 0.0, "adam_ms": 0.0, "spill_ms": 0.0}
-    link = {"h2d": 0, "d2h": 0, "min_h2d": 0, "min_d2h": 0, "moved_chunks": 0, "resident_chunks": []}
-    t0 = time.perf_counter()
-    skipped = 0
-    for i in range(a.steps):
-        before = list(st.loc)
-        skipped += run_step(st, not a.separate_check, plan_at(1 + a.warmup + i))
-        tm = psx.psx_ctx_get_timing(st.ctx)      # events of this step; the stream is already drained
-        phase["pack_ms"] += tm.pack_ms; phase["check_ms"] += tm.check_ms
-        phase["adam_ms"] += tm.adam_ms; phase["spill_ms"] += tm.spill_ms
-        if plans:
-            # every chunk that starts the step on the host must come in once, every chunk that ends it there
-            # must go out once: 12 bytes per used element each
-            link["h2d"] += int(tm.h2d_bytes); link["d2h"] += int(tm.d2h_bytes)
-            link["min_h2d"] += 12 * sum(u for u, l in zip(st.used, before) if l == psx.PSX_LOC_HOST)
-            link["min_d2h"] += 12 * sum(u for u, l in zip(st.used, st.loc) if l == psx.PSX_LOC_HOST)
-            link["moved_chunks"] += sum(x != y for x, y in zip(before, st.loc))
-            link["resident_chunks"].append(sum(l == psx.PSX_LOC_HBM for l in st.loc))
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms = dt * 1e3 / a.steps
+    r = timed_steps(st, a.steps, a.warmup, not a.separate_check, plans)
+    ms, phase, tm = r["ms"], r["phase"], r["tm"]
     n_elems = w.n_elems
-    for k in phase:
-        phase[k] /= a.steps
+    copy_gbs = plain_copy_rate(st.ctx, dev)
+    roofline = adam_roofline(r, copy_gbs)
+    traffic_file = os.path.join("profiles", "adam_kernel_gpt1b_hbm_traffic.txt")
+    roofline["traffic"] = read_traffic(os.path.join(ROOT, traffic_file)) if headline else None
+    # not a quantity of this run: HBM bytes per launch from the committed FETCH_SIZE / WRITE_SIZE counter runs
+    roofline["traffic_source"] = traffic_file if roofline["traffic"] is not None else None
     adam_elems = int(tm.adam_elems)
-    adam_bytes = ADAM_BYTES_PER_ELEM * adam_elems
-    achieved = adam_bytes / (phase["adam_ms"] * 1e-3) / 1e9 if phase["adam_ms"] > 0 else 0.0
-    traffic = read_traffic(os.path.join(ROOT, "profiles", "adam_kernel_gpt1b_hbm_traffic.txt")) \
-        if (a.workload == "gpt1b" and not a.layers and not a.chunk_elems and host_fraction == 0) else None
-    # a same-run yardstick for the roofline: this library's plain copy kernel over 1 GiB (1 read + 1 write stream)
-    nb = 1 << 30
-    src = torch.ones(nb // 4, dtype=torch.float32, device=dev)
-    dst = torch.zeros_like(src)
-    for _ in range(3):
-        psx.psx_copy_bytes(st.ctx, dst, src, nb)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(10):
-        psx.psx_copy_bytes(st.ctx, dst, src, nb)         # launched on torch's current stream, as the events are
-    e1.record()
-    torch.cuda.synchronize()
-    copy_gbs = 10 * 2 * nb / (e0.elapsed_time(e1) * 1e-3) / 1e9
-    del src, dst
     out = {
         "metric": "chunked Adam Gelem/s (whole hot path per step: layout + grad pack + overflow check + fused Adam + fp16 unpack + loss-scale update)",
         "value": n_elems / (ms * 1e-3) / 1e9,
@@ -370,45 +566,36 @@ def main():
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": w.name, "n_elems": n_elems, "n_tensors": len(w.numel), "chunk_elems": w.chunk_elems,
+        "config": {"workload": w.name, "scaled_from": scaled_from, "n_elems": n_elems, "n_tensors": len(w.numel),
+                   "chunk_elems": w.chunk_elems,
                    "n_chunks": st.nch, "host_resident_chunks": st.n_host, "host_chunks_on_host_cores": st.n_cpu,
                    "loss_scale": w.loss_scale,
-                   "weight_decay": w.weight_decay, "fused_check": not a.separate_check, "chunk_reuse": a.chunk_reuse, "skipped_steps": skipped},
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "kernel": "psx::adam_kernel (resident chunks, one launch)",
-                     "bytes_per_launch": adam_bytes, "avg_launch_ms": phase["adam_ms"],
-                     "same_run_plain_copy_GBs": copy_gbs, "frac_of_plain_copy": achieved / copy_gbs},
+                   "weight_decay": w.weight_decay, "fused_check": not a.separate_check, "chunk_reuse": a.chunk_reuse,
+                   "skipped_steps": r["skipped"]},
+        "roofline": roofline,
         "adam_only_gelem_s": adam_elems / (phase["adam_ms"] * 1e-3) / 1e9 if phase["adam_ms"] > 0 else None,
         "phase_ms": phase,
         "cpu_baseline": cpu,
     }
     if st.n_host:
-        link_s = phase["spill_ms"] * 1e-3
-        r = psx.psx_measure_link(st.ctx, 1024, 5)      # same copy streams as the pipeline, pinned memory
-        peak = {"copy_h2d_alone_GBs": r.h2d_alone, "copy_d2h_alone_GBs": r.d2h_alone,
-                "copy_each_way_both_at_once_GBs": r.each_way_both, "copy_MiB": 1024}
-        h2d = tm.h2d_bytes / link_s / 1e9 if link_s else None
-        # denominator: the best pinned-copy rate one direction reaches on this machine in this run (copies in
-        # both directions at once reach less than that with this runtime; both figures are listed)
-        out["host_link"] = {"bound": "host link, 12 B/element each way, both directions at once",
-                            "h2d_GBs": h2d, "d2h_GBs": tm.d2h_bytes / link_s / 1e9 if link_s else None,
-                            "measured_peak": peak,
-                            "frac": h2d / max(r.h2d_alone, r.d2h_alone) if h2d else None,
-                            "frac_of_copies_both_at_once": h2d / r.each_way_both if h2d else None,
-                            "host_cores": {"elems": int(tm.cpu_elems), "threads": int(tm.cpu_threads), "ms": float(tm.cpu_ms),
-                                           "gelem_s": tm.cpu_elems / (tm.cpu_ms * 1e-3) / 1e9 if tm.cpu_ms else None},
-                            "host_part_gelem_s": (tm.spill_elems + tm.cpu_elems) / link_s / 1e9 if link_s else None,
-                            "spill_elems": int(tm.spill_elems), "spill_ms": phase["spill_ms"],
-                            "spill_gelem_s": tm.spill_elems / link_s / 1e9 if link_s else None}
+        out["host_link"] = host_link_report(st, r, host_mode)
     if plans:
+        link = r["link"]
         moved = link["h2d"] + link["d2h"]
         floor = link["min_h2d"] + link["min_d2h"]
         out["residency"] = {"hbm_budget": f"{1.0 - host_fraction:.2f} of the fp32-state chunks, x (1 + {w.budget_jitter} u_t), u_t ~ U(-1, 1) seeded",
                             "resident_chunks_per_step": link["resident_chunks"], "chunks_that_changed_residence": link["moved_chunks"],
                             "link_bytes": moved, "link_bytes_minimum": floor, "link_bytes_over_minimum": moved / floor if floor else None}
+    if a.sweep_wg:
+        out["wg_per_cu_sweep"] = sweep_wg(st, [int(x) for x in a.sweep_wg.split(",")])
+    if legs:
+        # the other halves of the metric, each a short run of its own after the timed headline:
+        # the paper's chunk-reuse layout, host-resident chunks over the link, and on the host cores
+        out["chunk_reuse"] = leg_chunk_reuse(st)
+    release(st)
+    if legs:
+        out["host_link"], out["host_cores"] = leg_host(a, dev)
     print(json.dumps(out))
-    psx.psx_ctx_destroy(st.ctx)
 
 
 if __name__ == "__main__":
