@@ -98,6 +98,27 @@ struct TimedSpan {
 
 }  // namespace
 
+namespace {
+
+struct CpuTile {
+    const uint16_t *g16;   // device
+    uint16_t *p16;         // device
+    float *p, *m, *v;      // pinned host, updated in place
+    uint64_t n;
+    bool alias;
+};
+
+struct SpillTile {
+    size_t run;            // index into the table (its AdamRun)
+    const float *src[3];   // host sources (H2D) or NULL
+    float *stage[3];       // device targets of the H2D / sources of the D2H
+    float *dst[3];         // host targets (D2H) or NULL
+    uint64_t n;
+    bool alias;
+};
+
+}  // namespace
+
 struct psx_ctx {
     int device = 0;
     int n_cu = 0;
@@ -118,6 +139,11 @@ struct psx_ctx {
     std::vector<MoveRun> moves;
     std::vector<CopySeg> segs;
     std::vector<unsigned char> blob;   // scratch: descriptors + first tiles, as uploaded
+    std::vector<SpillTile> spill_tiles;   // scratch of psx_chunk_adam_step (kept to keep their capacity)
+    std::vector<CpuTile> cpu_tiles;
+    // pinned ranges already shown to be device-accessible, by chunk index: {p32_host, m_host, v_host, used}
+    struct HostSeen { const void *p[3]; uint64_t used; };
+    std::vector<HostSeen> host_seen;
     int copy_unroll_now = 1;           // tile shape the segments in `segs` were cut for
     // host-core execution (PSX_EXEC_CPU), allocated on first use
     CpuPool *pool = nullptr;
@@ -665,23 +691,6 @@ int32_t ensure_cpu(psx_ctx *c) {
     return PSX_OK;
 }
 
-struct CpuTile {
-    const uint16_t *g16;   // device
-    uint16_t *p16;         // device
-    float *p, *m, *v;      // pinned host, updated in place
-    uint64_t n;
-    bool alias;
-};
-
-struct SpillTile {
-    size_t run;            // index into the table (its AdamRun)
-    const float *src[3];   // host sources (H2D) or NULL
-    float *stage[3];       // device targets of the H2D / sources of the D2H
-    float *dst[3];         // host targets (D2H) or NULL
-    uint64_t n;
-    bool alias;
-};
-
 }  // namespace
 
 extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size_t n_chunks,
@@ -726,8 +735,15 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
             if (staged && T == 0) return fail(PSX_ENOSTAGING, "psx_chunk_adam_step: chunk %zu is host-resident but the context has no staging", k);
             if (!staged && ch.exec != PSX_EXEC_CPU) {
                 // the kernel will dereference these host pointers: they must be page-locked memory the
-                // device can reach, over their whole used range, or the launch would fault the GPU
+                // device can reach, over their whole used range, or the launch would fault the GPU.
+                // Asking the driver costs microseconds per pointer, so a chunk whose three ranges are the
+                // ones this context saw at the same index last time is not asked about again (the caller
+                // keeps a host-resident chunk's buffers page-locked while it passes them).
                 const void *hp[3] = {ch.p32_host, ch.m_host, ch.v_host};
+                if (c->host_seen.size() < n_chunks) c->host_seen.resize(n_chunks, psx_ctx::HostSeen{{nullptr, nullptr, nullptr}, 0});
+                psx_ctx::HostSeen &seen = c->host_seen[k];
+                if (seen.p[0] == hp[0] && seen.p[1] == hp[1] && seen.p[2] == hp[2] && seen.used >= ch.used) continue;
+                seen = psx_ctx::HostSeen{{nullptr, nullptr, nullptr}, 0};
                 for (int j = 0; j < 3; j++) {
                     const char *ends[2] = {static_cast<const char *>(hp[j]), static_cast<const char *>(hp[j]) + (ch.used * sizeof(float) - 1)};
                     for (const char *q : ends) {
@@ -740,6 +756,7 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
                         }
                     }
                 }
+                seen = psx_ctx::HostSeen{{hp[0], hp[1], hp[2]}, ch.used};
             }
         }
     }
@@ -774,8 +791,10 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
         }
     const size_t n_check = c->runs.size() - n_res - n_recast;
 
-    std::vector<SpillTile> tiles;
-    std::vector<CpuTile> cpu_tiles;
+    std::vector<SpillTile> &tiles = c->spill_tiles;
+    std::vector<CpuTile> &cpu_tiles = c->cpu_tiles;
+    tiles.clear();
+    cpu_tiles.clear();
     uint64_t cpu_elems = 0;
     uint64_t spill_elems = 0, h2d_bytes = 0, d2h_bytes = 0;
     uint64_t slot_counter = 0;
@@ -917,113 +936,132 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
         PSX_HIP(hipEventRecord(c->ev_flag, s));
     }
 
-    // ---- HBM-resident chunks: one launch over all of them
-    c->adam_elems = res_elems;
-    c->t_adam.valid = false;
-    if (res_tiles != 0) {
-        if ((rc = span_begin(c, c->t_adam, s)) != PSX_OK) return rc;
-        PSX_HIP(launch_adam(view(0, n_res), res_tiles, sc, flag, c->tune, c->n_cu, s));
-        if ((rc = span_end(c, c->t_adam, s)) != PSX_OK) return rc;
-        if (n_recast != 0)
-            PSX_HIP(launch_recast_if_flag(view(n_res, n_recast), recast_tiles, flag, c->tune, c->n_cu, s));
-    }
-
-    // ---- host-resident chunks, direct mode: one persistent launch on the side stream, concurrent with
-    // the resident launch; every load and store of p/m/v crosses the host link once, in both directions at once
-    c->spill_elems = spill_elems; c->h2d_bytes = h2d_bytes; c->d2h_bytes = d2h_bytes;
+    // Everything from here on is enqueued inside one function, so that whatever it returns the side
+    // streams are joined back into the caller's stream below: after an error part of the work may be
+    // running on them, and the caller's next work on `stream` must still come after it.
     bool any_h2d = false, any_d2h = false;
-    if (n_direct != 0 || move_tiles != 0) {
-        if (n_direct != 0)
-            PSX_HIP(launch_adam(view(direct_off, n_direct), direct_tiles, sc, flag, td, c->n_cu, c->h2d));
-        if (move_tiles != 0)
-            PSX_HIP(launch_adam_move(MoveView{mtbl, mtbl_begins, (uint32_t)c->moves.size()}, move_tiles, sc, flag, c->tune,
-                                     (uint32_t)c->tune.host_grid, c->h2d));
-        if (n_direct_recast != 0)
-            PSX_HIP(launch_recast_if_flag(view(direct_off + n_direct, n_direct_recast), direct_recast_tiles, flag, td, c->n_cu, c->h2d));
-        any_h2d = true;
-    }
+    auto enqueue = [&]() -> int32_t {
+        // ---- HBM-resident chunks: one launch over all of them
+        c->adam_elems = res_elems;
+        c->t_adam.valid = false;
+        if (res_tiles != 0) {
+            if ((rc = span_begin(c, c->t_adam, s)) != PSX_OK) return rc;
+            PSX_HIP(launch_adam(view(0, n_res), res_tiles, sc, flag, c->tune, c->n_cu, s));
+            if ((rc = span_end(c, c->t_adam, s)) != PSX_OK) return rc;
+            if (n_recast != 0)
+                PSX_HIP(launch_recast_if_flag(view(n_res, n_recast), recast_tiles, flag, c->tune, c->n_cu, s));
+        }
 
-    // ---- chunks with a host side, staged: H2D (copy stream) -> update (caller's stream) -> D2H (copy stream)
-    const size_t ring = c->ev_k.size();
-    for (size_t i = 0; i < tiles.size(); i++) {
-        const SpillTile &t = tiles[i];
-        const size_t e = i % ring;
-        const size_t bytes = t.n * sizeof(float);
-        if (t.src[0] != nullptr) {
-            if (i >= ring) PSX_HIP(hipStreamWaitEvent(c->h2d, c->ev_free[e], 0));   // staging slot drained
-            for (int j = 0; j < 3; j++)
-                PSX_HIP(hipMemcpyAsync(t.stage[j], t.src[j], bytes, hipMemcpyHostToDevice, c->h2d));
-            PSX_HIP(hipEventRecord(c->ev_h2d[e], c->h2d));
-            PSX_HIP(hipStreamWaitEvent(s, c->ev_h2d[e], 0));
+        // ---- host-resident chunks, direct mode: one persistent launch on the side stream, concurrent with
+        // the resident launch; every load and store of p/m/v crosses the host link once, in both directions at once
+        c->spill_elems = spill_elems; c->h2d_bytes = h2d_bytes; c->d2h_bytes = d2h_bytes;
+        if (n_direct != 0 || move_tiles != 0) {
+            if (n_direct != 0)
+                PSX_HIP(launch_adam(view(direct_off, n_direct), direct_tiles, sc, flag, td, c->n_cu, c->h2d));
+            if (move_tiles != 0)
+                PSX_HIP(launch_adam_move(MoveView{mtbl, mtbl_begins, (uint32_t)c->moves.size()}, move_tiles, sc, flag, c->tune,
+                                         (uint32_t)c->tune.host_grid, c->h2d));
+            if (n_direct_recast != 0)
+                PSX_HIP(launch_recast_if_flag(view(direct_off + n_direct, n_direct_recast), direct_recast_tiles, flag, td, c->n_cu, c->h2d));
             any_h2d = true;
         }
-        Tuning tn = c->tune;
-        PSX_HIP(launch_adam(view(t.run, 1), (t.n + adam_tile - 1) / adam_tile, sc, flag, tn, c->n_cu, s));
-        if (use_flag && t.alias)
-            PSX_HIP(launch_recast_if_flag(view(t.run, 1), (t.n + recast_tile - 1) / recast_tile, flag, tn, c->n_cu, s));
-        if (t.dst[0] != nullptr) {
-            PSX_HIP(hipEventRecord(c->ev_k[e], s));
-            PSX_HIP(hipStreamWaitEvent(c->d2h, c->ev_k[e], 0));
-            for (int j = 0; j < 3; j++)
-                PSX_HIP(hipMemcpyAsync(t.dst[j], t.stage[j], bytes, hipMemcpyDeviceToHost, c->d2h));
-            PSX_HIP(hipEventRecord(c->ev_free[e], c->d2h));
-            any_d2h = true;
-        } else {
-            PSX_HIP(hipEventRecord(c->ev_free[e], s));
-        }
-    }
-    // ---- host-resident chunks executed by the host cores: everything above is already running on the GPU;
-    // this thread now pipelines  D2H fp16 gradient tile -> update of p/m/v in place -> H2D fp16 parameter tile
-    c->cpu_elems = cpu_elems;
-    c->cpu_ms = 0.0f;
-    if (any_cpu) {
-        bool skip = false;
-        if (use_flag) {
-            PSX_HIP(hipEventSynchronize(c->ev_flag));
-            skip = c->flags_host[0] != 0;
-        }
-        if (skip) {                                   // nothing to update; aliased fp16 chunks get their params back
-            size_t w = 0;
-            for (size_t i = 0; i < cpu_tiles.size(); i++)
-                if (cpu_tiles[i].alias) cpu_tiles[w++] = cpu_tiles[i];
-            cpu_tiles.resize(w);
-        }
-        PSX_HIP(hipEventSynchronize(c->ev_cpu_end));   // the previous call's uploads have left the staging
-        const auto t0 = std::chrono::steady_clock::now();
-        const size_t nt = cpu_tiles.size();
-        size_t issued = 0;
-        auto fetch = [&](size_t i) -> int32_t {
-            const int slot = (int)(i % kCpuSlots);
-            PSX_HIP(hipMemcpyAsync(c->cpu_g[slot], cpu_tiles[i].g16, cpu_tiles[i].n * 2, hipMemcpyDeviceToHost, c->d2h));
-            PSX_HIP(hipEventRecord(c->ev_cg[slot], c->d2h));
-            return PSX_OK;
-        };
-        if (!skip)
-            for (; issued < nt && issued < (size_t)kCpuSlots; issued++)
-                if ((rc = fetch(issued)) != PSX_OK) return rc;
-        for (size_t i = 0; i < nt; i++) {
-            const CpuTile &t = cpu_tiles[i];
-            const int slot = (int)(i % kCpuSlots);
-            if (!skip) PSX_HIP(hipEventSynchronize(c->ev_cg[slot]));            // gradient tile has arrived
-            if (i >= (size_t)kCpuSlots) PSX_HIP(hipEventSynchronize(c->ev_ch[slot]));   // parameter staging sent
-            if (!skip) cpu_adam_tile(c->pool, c->cpu_g[slot], c->cpu_h[slot], t.p, t.m, t.v, t.n, sc, c->tune.cpu_isa);
-            else cpu_recast_tile(c->pool, c->cpu_h[slot], t.p, t.n);
-            PSX_HIP(hipMemcpyAsync(t.p16, c->cpu_h[slot], t.n * 2, hipMemcpyHostToDevice, c->aux));
-            PSX_HIP(hipEventRecord(c->ev_ch[slot], c->aux));
-            if (!skip && issued < nt) {               // this slot's gradient staging is free again
-                if ((rc = fetch(issued)) != PSX_OK) return rc;
-                issued++;
+
+        // ---- chunks with a host side, staged: H2D (copy stream) -> update (caller's stream) -> D2H (copy stream)
+        const size_t ring = c->ev_k.size();
+        for (size_t i = 0; i < tiles.size(); i++) {
+            const SpillTile &t = tiles[i];
+            const size_t e = i % ring;
+            const size_t bytes = t.n * sizeof(float);
+            if (t.src[0] != nullptr) {
+                if (i >= ring) PSX_HIP(hipStreamWaitEvent(c->h2d, c->ev_free[e], 0));   // staging slot drained
+                for (int j = 0; j < 3; j++)
+                    PSX_HIP(hipMemcpyAsync(t.stage[j], t.src[j], bytes, hipMemcpyHostToDevice, c->h2d));
+                PSX_HIP(hipEventRecord(c->ev_h2d[e], c->h2d));
+                PSX_HIP(hipStreamWaitEvent(s, c->ev_h2d[e], 0));
+                any_h2d = true;
+            }
+            Tuning tn = c->tune;
+            PSX_HIP(launch_adam(view(t.run, 1), (t.n + adam_tile - 1) / adam_tile, sc, flag, tn, c->n_cu, s));
+            if (use_flag && t.alias)
+                PSX_HIP(launch_recast_if_flag(view(t.run, 1), (t.n + recast_tile - 1) / recast_tile, flag, tn, c->n_cu, s));
+            if (t.dst[0] != nullptr) {
+                PSX_HIP(hipEventRecord(c->ev_k[e], s));
+                PSX_HIP(hipStreamWaitEvent(c->d2h, c->ev_k[e], 0));
+                for (int j = 0; j < 3; j++)
+                    PSX_HIP(hipMemcpyAsync(t.dst[j], t.stage[j], bytes, hipMemcpyDeviceToHost, c->d2h));
+                PSX_HIP(hipEventRecord(c->ev_free[e], c->d2h));
+                any_d2h = true;
+            } else {
+                PSX_HIP(hipEventRecord(c->ev_free[e], s));
             }
         }
-        PSX_HIP(hipEventRecord(c->ev_cpu_end, c->aux));
-        PSX_HIP(hipStreamWaitEvent(s, c->ev_cpu_end, 0));
-        any_d2h = true;
-        c->cpu_ms = std::chrono::duration<float, std::milli>(std::chrono::steady_clock::now() - t0).count();
-    }
+        // ---- host-resident chunks executed by the host cores: everything above is already running on the GPU;
+        // this thread now pipelines  D2H fp16 gradient tile -> update of p/m/v in place -> H2D fp16 parameter tile
+        c->cpu_elems = cpu_elems;
+        c->cpu_ms = 0.0f;
+        if (any_cpu) {
+            bool skip = false;
+            if (use_flag) {
+                PSX_HIP(hipEventSynchronize(c->ev_flag));
+                skip = c->flags_host[0] != 0;
+            }
+            if (skip) {                                   // nothing to update; aliased fp16 chunks get their params back
+                size_t w = 0;
+                for (size_t i = 0; i < cpu_tiles.size(); i++)
+                    if (cpu_tiles[i].alias) cpu_tiles[w++] = cpu_tiles[i];
+                cpu_tiles.resize(w);
+            }
+            PSX_HIP(hipEventSynchronize(c->ev_cpu_end));   // the previous call's uploads have left the staging
+            const auto t0 = std::chrono::steady_clock::now();
+            const size_t nt = cpu_tiles.size();
+            size_t issued = 0;
+            auto fetch = [&](size_t i) -> int32_t {
+                const int slot = (int)(i % kCpuSlots);
+                PSX_HIP(hipMemcpyAsync(c->cpu_g[slot], cpu_tiles[i].g16, cpu_tiles[i].n * 2, hipMemcpyDeviceToHost, c->d2h));
+                PSX_HIP(hipEventRecord(c->ev_cg[slot], c->d2h));
+                return PSX_OK;
+            };
+            if (!skip)
+                for (; issued < nt && issued < (size_t)kCpuSlots; issued++)
+                    if ((rc = fetch(issued)) != PSX_OK) return rc;
+            for (size_t i = 0; i < nt; i++) {
+                const CpuTile &t = cpu_tiles[i];
+                const int slot = (int)(i % kCpuSlots);
+                if (!skip) PSX_HIP(hipEventSynchronize(c->ev_cg[slot]));            // gradient tile has arrived
+                if (i >= (size_t)kCpuSlots) PSX_HIP(hipEventSynchronize(c->ev_ch[slot]));   // parameter staging sent
+                if (!skip) cpu_adam_tile(c->pool, c->cpu_g[slot], c->cpu_h[slot], t.p, t.m, t.v, t.n, sc, c->tune.cpu_isa);
+                else cpu_recast_tile(c->pool, c->cpu_h[slot], t.p, t.n);
+                PSX_HIP(hipMemcpyAsync(t.p16, c->cpu_h[slot], t.n * 2, hipMemcpyHostToDevice, c->aux));
+                PSX_HIP(hipEventRecord(c->ev_ch[slot], c->aux));
+                if (!skip && issued < nt) {               // this slot's gradient staging is free again
+                    if ((rc = fetch(issued)) != PSX_OK) return rc;
+                    issued++;
+                }
+            }
+            PSX_HIP(hipEventRecord(c->ev_cpu_end, c->aux));
+            PSX_HIP(hipStreamWaitEvent(s, c->ev_cpu_end, 0));
+            any_d2h = true;
+            c->cpu_ms = std::chrono::duration<float, std::milli>(std::chrono::steady_clock::now() - t0).count();
+        }
+        return PSX_OK;
+    };
+    const int32_t rc_enqueue = enqueue();
     if (any_side) {
-        if (any_h2d) { PSX_HIP(hipEventRecord(c->ev_h2d_end, c->h2d)); PSX_HIP(hipStreamWaitEvent(s, c->ev_h2d_end, 0)); }
-        if (any_d2h) { PSX_HIP(hipEventRecord(c->ev_d2h_end, c->d2h)); PSX_HIP(hipStreamWaitEvent(s, c->ev_d2h_end, 0)); }
+        // on the error path every side stream that may hold work is joined, whatever was reached
+        const bool all = rc_enqueue != PSX_OK;
+        int32_t rc_join = PSX_OK;
+        auto join = [&](hipStream_t side, hipEvent_t ev) {
+            hipError_t e = hipEventRecord(ev, side);
+            if (e == hipSuccess) e = hipStreamWaitEvent(s, ev, 0);
+            if (e != hipSuccess && rc_join == PSX_OK && rc_enqueue == PSX_OK)
+                rc_join = fail(PSX_EHIP, "psx_chunk_adam_step: joining a side stream -> %s", hipGetErrorString(e));
+        };
+        if (any_h2d || all) join(c->h2d, c->ev_h2d_end);
+        if (any_d2h || all) join(c->d2h, c->ev_d2h_end);
+        if (all && any_cpu && c->aux != nullptr) join(c->aux, c->ev_cpu_end);
+        if (rc_enqueue != PSX_OK) return rc_enqueue;
+        if (rc_join != PSX_OK) return rc_join;
         if (c->prof) { PSX_HIP(hipEventRecord(c->t_spill.b, s)); c->t_spill.valid = true; }
     }
-    return PSX_OK;
+    return rc_enqueue;
 }

@@ -318,6 +318,43 @@ def test_fp16_recast_is_round_to_nearest_even(orc, ctx):
         assert np.array_equal(bits16(cl.p16[0])[:n], vals.astype(np.float16).view(np.uint16))
 
 
+def test_fp16_recast_of_every_fp32_bit_pattern(orc, ctx):
+    """All 2^32 fp32 bit patterns through the kernels' fp32 -> fp16 conversion (the skipped-step re-cast of a
+    reused fp16 chunk), in windows of 2^28, bit for bit against the oracle's conversion.  NaN inputs are
+    compared by class: the result must be a NaN of the same sign (which payload bits survive is not
+    part of the format's rounding rule)."""
+    from concurrent.futures import ThreadPoolExecutor
+    W28 = 1 << 28
+    p32 = torch.empty(W28, dtype=torch.int32, device=DEV)
+    m = torch.zeros(W28, dtype=torch.float32, device=DEV)
+    h16 = torch.empty(W28, dtype=torch.int16, device=DEV)
+    idx = torch.arange(W28, dtype=torch.int64, device=DEV)
+    spec = [dict(g16=h16, p16=h16, p32=p32, m=m, v=m, used=W28)]      # m and v are never written on a skipped step
+    chunks = psx.make_chunks(spec)
+    parts = 16
+    pool = ThreadPoolExecutor(parts)
+    for win in range(16):
+        base = win * W28
+        p32.copy_((idx + base).to(torch.int32))                       # wraps into the negative half: the bit pattern counts
+        h16.zero_()
+        h16[12345] = 0x7C00                                           # an inf gradient: the step is skipped, p16 = fp16(p32)
+        psx.psx_chunk_adam_step(ctx, chunks, psx.make_hyper(step=1, loss_scale=1.0), psx.PSX_STEP_CHECK_FIRST)
+        flag, _ = psx.psx_overflow_read(ctx)
+        assert flag == 1
+        got = h16.cpu().numpy().view(np.uint16)
+        bits = np.arange(base, base + W28, dtype=np.uint64).astype(np.uint32)
+        step = W28 // parts
+        want = np.concatenate(list(pool.map(lambda j: orc.f32_to_f16(bits[j * step:(j + 1) * step].view(np.float32)), range(parts))))
+        isnan = (bits & 0x7FFFFFFF) > 0x7F800000
+        assert np.array_equal(got[~isnan], want[~isnan]), f"window {win}: {np.count_nonzero(got[~isnan] != want[~isnan])} differ"
+        if isnan.any():
+            g = got[isnan]
+            assert np.all((g & 0x7C00) == 0x7C00) and np.all((g & 0x03FF) != 0), f"window {win}: a NaN became a number"
+            assert np.array_equal(g & 0x8000, ((bits[isnan] >> 16) & 0x8000).astype(np.uint16)), f"window {win}: NaN sign"
+    assert not m.any()
+    pool.shutdown()
+
+
 # ---------------------------------------------------------------------------------- skip semantics
 
 @pytest.mark.parametrize("alias", [False, True])
