@@ -77,6 +77,7 @@ struct Tuning {
     int host_grid = 32;            // direct mode: persistent workgroups (256 threads) of the host launch
     int host_unroll = 1;           // direct mode: rows of 4 elements per thread
     int grid_override = 0;         // internal: absolute grid size of a launch (0: derive from blocks_per_cu)
+    int lds_per_cu = 160 * 1024;   // internal: LDS bytes of one CU as the device reports them (what the occupancy cap divides)
     int cpu_threads = 0;           // PSX_EXEC_CPU: worker threads (0: min(hardware threads, 16))
     uint64_t cpu_tile_elems = 4u << 20;   // PSX_EXEC_CPU: elements per pipeline tile
     int cpu_isa = 0;               // PSX_EXEC_CPU: 0 widest vectors the host has (AVX-512 or AVX2), 1 AVX2
@@ -111,6 +112,9 @@ struct SegView {
     const uint64_t *begins;
     uint32_t n;
 };
+
+// LDS bytes per CU of `device` as the runtime reports them; 160 KiB (gfx950) if it reports nothing usable.
+int query_lds_per_cu(int device);
 
 // ---- launchers (psx_kernels.hip).  All enqueue on `s` and return the launch status. ----
 hipError_t launch_adam(const RunView &rv, uint64_t n_tiles,

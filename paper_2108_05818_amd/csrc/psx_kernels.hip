@@ -187,11 +187,23 @@ static hipError_t launch_adam_u(int unroll, const RunView &rv, uint64_t n_tiles,
 }
 
 // Bytes of LDS to reserve per workgroup so that at most wg_per_cu workgroups
-// fit the 160 KiB of a CU (0 = no cap).  The kernels never touch it.
-static uint32_t throttle_lds(int wg_per_cu) {
+// fit the LDS of a CU (0 = no cap).  The kernels never touch it.
+static uint32_t throttle_lds(int wg_per_cu, int lds_per_cu) {
     if (wg_per_cu <= 0) return 0;
-    if (wg_per_cu < 3) wg_per_cu = 3;                    // stay under the 64 KiB dynamic-LDS default
-    return (uint32_t)((160u * 1024u / (uint32_t)wg_per_cu) & ~511u);
+    uint32_t bytes = ((uint32_t)lds_per_cu / (uint32_t)wg_per_cu) & ~511u;
+    if (bytes > 64u * 1024u - 512u) bytes = 64u * 1024u - 512u;   // stay under the 64 KiB a launch may ask for by default
+    return bytes;
+}
+
+int query_lds_per_cu(int device) {
+    int v = 0;
+    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, device) != hipSuccess) {
+        (void)hipGetLastError();
+        v = 0;
+    }
+    // a CU's LDS is never smaller than what one workgroup may use (64 KiB); anything below that is not a
+    // per-CU figure, and the chip this library is written for has 160 KiB
+    return v >= 64 * 1024 ? v : 160 * 1024;
 }
 
 // blocks_per_cu == 0: one tile per workgroup, handed out in order by the dispatcher.
@@ -207,7 +219,7 @@ hipError_t launch_adam(const RunView &rv, uint64_t n_tiles, const AdamScalars &s
     if (n_tiles == 0) return hipSuccess;
     const uint32_t grid = t.grid_override > 0 ? (uint32_t)(n_tiles < (uint64_t)t.grid_override ? n_tiles : (uint64_t)t.grid_override)
                                               : grid_for(n_tiles, t.adam_blocks_per_cu, n_cu);
-    const uint32_t lds = throttle_lds(t.adam_wg_per_cu);
+    const uint32_t lds = throttle_lds(t.adam_wg_per_cu, t.lds_per_cu);
     const bool nt = t.nontemporal != 0;
     if (t.adam_threads == 64)
         return nt ? launch_adam_u<64, true>(t.adam_unroll, rv, n_tiles, sc, flag, grid, lds, s)

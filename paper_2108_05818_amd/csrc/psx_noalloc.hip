@@ -51,6 +51,7 @@ __global__ void flag_copy_kernel(uint32_t *dst, const uint32_t *src) {
 struct DevState {
     unsigned char *ptr = nullptr;   // this device's address of `scratch`
     int n_cu = 0;
+    int lds_per_cu = 0;
 };
 DevState g_dev[kMaxDevices];
 std::mutex g_mu;
@@ -67,6 +68,7 @@ int32_t dev_state(int device, DevState *out) {
         int n_cu = 0;
         PSX_HIP(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, device));
         d.n_cu = n_cu > 0 ? n_cu : 256;
+        d.lds_per_cu = query_lds_per_cu(device);
         d.ptr = static_cast<unsigned char *>(p);
     }
     *out = d;
@@ -138,7 +140,8 @@ extern "C" int32_t psx_chunk_adam_step_noalloc(const psx_chunk *chunks, size_t n
     uint32_t *flags_dev = reinterpret_cast<uint32_t *>(d.ptr);
     AdamRun *runs_dev = reinterpret_cast<AdamRun *>(d.ptr + kRunsOff);
     uint64_t *begins_dev = reinterpret_cast<uint64_t *>(d.ptr + kBeginsOff);
-    const Tuning tune;                                   // the library's default launch shapes
+    Tuning tune;                                         // the library's default launch shapes
+    tune.lds_per_cu = d.lds_per_cu;
     const uint64_t tile_elems[kSections] = {adam_tile_elems(tune), kRecastTileElems, kCheckTileElems};
 
     // ---- descriptor tables: every section is rewritten by every call (the array keeps the last call's content)

@@ -216,6 +216,7 @@ extern "C" int32_t psx_ctx_create(const psx_ctx_config *cfg, psx_ctx **out) {
     PSX_TRY(hipGetDevice(&c->device));
     PSX_TRY(hipDeviceGetAttribute(&c->n_cu, hipDeviceAttributeMultiprocessorCount, c->device));
     if (c->n_cu <= 0) c->n_cu = 256;
+    c->tune.lds_per_cu = query_lds_per_cu(c->device);
     c->flags_n = 1 + (size_t)cfg->max_chunks;
     PSX_TRY(hipMalloc(reinterpret_cast<void **>(&c->flags_dev), c->flags_n * sizeof(uint32_t)));
     PSX_TRY(hipHostMalloc(reinterpret_cast<void **>(&c->flags_host), c->flags_n * sizeof(uint32_t), hipHostMallocDefault));
