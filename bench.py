@@ -50,6 +50,9 @@ def parse():
     ap.add_argument("--sweep-wg", default="", metavar="LIST",
                     help="after the timed steps, time the Adam launch with each of these caps on resident workgroups "
                          "per CU (comma list, 0 = no cap), all in the same allocation")
+    ap.add_argument("--placements", type=int, default=0, metavar="N",
+                    help="after the timed steps, free everything and set the headline workload up again N times "
+                         "(alternating chunk reuse off / on), timing the Adam launch in each placement")
     ap.add_argument("--no-legs", action="store_true",
                     help="default run only: skip the extra legs (chunk reuse on the same workload; GPT-12.6B with "
                          "40 %% of the chunks host-resident, over the link and on the host cores)")
@@ -445,6 +448,22 @@ def leg_chunk_reuse(st):
             "bytes_of_chunk_lists_per_param": 14, "roofline": adam_roofline(r)}
 
 
+def placement_trials(a, dev, n):
+    """The Adam launch time over n fresh set-ups of the headline workload in this process, alternating a
+    gradient list of its own with chunk reuse.  Every set-up frees and re-allocates all buffers, so the
+    virtual addresses repeat while the physical placement changes: what varies between trials of one
+    kind is where the chunk lists landed in HBM."""
+    from paper_2108_05818_amd import workloads as W
+    out = []
+    for t in range(n):
+        w = W.config2_gpt1b()
+        st = setup(w, dev, keep_params=0, chunk_reuse=bool(t % 2))
+        r = timed_steps(st, 8, 3, True)
+        out.append({"trial": t, "chunk_reuse": bool(t % 2), "adam_ms": r["phase"]["adam_ms"], "frac": adam_roofline(r)["frac"]})
+        release(st)
+    return out
+
+
 def sweep_wg(st, values):
     """Adam launch time against the cap on resident workgroups per CU, in one allocation (so the
     placement of the buffers in memory is the same for every value)."""
@@ -593,6 +612,8 @@ def main():
         # the paper's chunk-reuse layout, host-resident chunks over the link, and on the host cores
         out["chunk_reuse"] = leg_chunk_reuse(st)
     release(st)
+    if a.placements:
+        out["placement_trials"] = placement_trials(a, dev, a.placements)
     if legs:
         out["host_link"], out["host_cores"] = leg_host(a, dev)
     print(json.dumps(out))
