@@ -204,7 +204,10 @@ typedef struct psx_adam_hyper {
  *   HOST -> HOST : by default the kernel reads and writes the pinned buffers
  *                  directly over the host link (one launch on a side stream,
  *                  concurrent with the resident chunks; the buffers must be
- *                  device-accessible, as hipHostMalloc memory is); with
+ *                  device-accessible, as hipHostMalloc memory is: the call asks the
+ *                  runtime about them the first time this context sees them at
+ *                  that chunk index and must find them page-locked from then on,
+ *                  for as long as the caller passes them); with
  *                  PSX_TUNE_HOST_MODE 0 they are streamed tile by tile through
  *                  the context's staging (H2D, update, D2H).  p32/m/v may be NULL.
  *   HOST -> HBM  : chunk admitted: the kernel reads the pinned buffers and

@@ -339,8 +339,10 @@ __global__ __launch_bounds__(kThreads) void recast_kernel(const AdamRun *__restr
 hipError_t launch_recast_if_flag(const RunView &rv, uint64_t n_tiles,
                                  const uint32_t *flag, const Tuning &t, int n_cu, hipStream_t s) {
     if (n_tiles == 0) return hipSuccess;
-    const uint32_t grid = t.grid_override > 0 ? (uint32_t)(n_tiles < (uint64_t)t.grid_override ? n_tiles : (uint64_t)t.grid_override)
-                                              : grid_for(n_tiles, t.adam_blocks_per_cu, n_cu);
+    // A persistent grid: on all steps but the rare skipped one every workgroup only reads the flag and leaves, and a
+    // launch of one workgroup per tile would spend 0.1 ms per 10^9 elements on that.
+    const uint64_t cap = t.grid_override > 0 ? (uint64_t)t.grid_override : (uint64_t)n_cu * 16u;
+    const uint32_t grid = (uint32_t)(n_tiles < cap ? n_tiles : cap);
     hipLaunchKernelGGL(recast_kernel, dim3(grid), dim3(kThreads), 0, s, rv.runs, rv.begins, rv.n, n_tiles, flag);
     return hipGetLastError();
 }
