@@ -53,6 +53,9 @@ def parse():
     ap.add_argument("--placements", type=int, default=0, metavar="N",
                     help="after the timed steps, free everything and set the headline workload up again N times "
                          "(alternating chunk reuse off / on), timing the Adam launch in each placement")
+    ap.add_argument("--device-state", action="store_true",
+                    help="also time the steps with t, the loss scale and the loss-scale bookkeeping on the device (no read-back per step)")
+    ap.add_argument("--graph", action="store_true", help="as --device-state, with the step recorded once into a HIP graph and replayed")
     ap.add_argument("--no-legs", action="store_true",
                     help="default run only: skip the extra legs (chunk reuse on the same workload; GPT-12.6B with "
                          "40 %% of the chunks host-resident, over the link and on the host cores)")
@@ -202,6 +205,77 @@ def run_step(st, fused_check=False, new_loc=None):
     flag, _ = psx.psx_overflow_read(ctx)                                      # synchronises the stream
     psx.psx_loss_scale_update(st.scaler, flag)                                # a7
     return flag
+
+
+def step_on_device(st):
+    """One pass of the hot path with nothing read back: the update takes t and the loss scale from the
+    context's step state on the device and the loss-scale bookkeeping (a7) runs there too.  Kernel
+    launches only once the descriptor tables are on the device, so it can be recorded into a HIP graph."""
+    from paper_2108_05818_amd import psx
+    ctx, C, n = st.ctx, st.C, len(st.numel_arr)
+    psx.psx_overflow_reset(ctx)
+    psx.psx_pack(ctx, psx.PSX_F16, st.t_ptrs, st.slots_c, st.g16, C, flags=psx.PSX_PACK_CHECK_OVERFLOW, n=n)
+    psx.psx_chunk_adam_step(ctx, st.chunks, st.hyper_dev, psx.PSX_STEP_USE_FLAG | psx.PSX_STEP_DEVICE_STATE, n_chunks=st.nch)
+    psx.psx_unpack(ctx, psx.PSX_F16, st.o_ptrs, st.slots_c, st.p16, C, n=n)
+    psx.psx_step_state_advance(ctx)
+
+
+def timed_steps_on_device(st, steps, warmup, graph):
+    """Steps that never synchronise (step state on the device), eagerly enqueued or as replays of one HIP
+    graph; the layout call (host) is still made every step.  Returns wall ms per step and the state read
+    back at the end."""
+    import torch
+    from paper_2108_05818_amd import psx
+    w = st.w
+    st.hyper_dev = psx.make_hyper(lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps, weight_decay=w.weight_decay,
+                                  adamw_mode=w.adamw_mode)
+    psx.psx_ctx_set_profiling(st.ctx, 0)
+    psx.psx_step_state_init(st.ctx, st.hyper_dev, st.scaler)
+    nch_out = ctypes.c_size_t(0)
+
+    def layout():
+        rc = psx.lib().psx_chunk_layout(st.numel_c, len(st.numel_arr), st.C, 0, st.slots_c, st.used_c, st.nch, ctypes.byref(nch_out))
+        if rc != 0:
+            raise RuntimeError(psx.psx_last_error())
+    layout()
+    for _ in range(max(warmup, 1)):            # also uploads the descriptor tables the recorded calls rely on
+        layout(); step_on_device(st)
+    torch.cuda.synchronize()
+    g = None
+    if graph:
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            step_on_device(st)
+        torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        layout()
+        if g is not None:
+            g.replay()
+        else:
+            step_on_device(st)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / max(steps, 1)
+    sc, last_flag, skipped = psx.psx_step_state_read(st.ctx)
+    return {"ms": ms, "step": int(sc.step), "scale": float(sc.scale), "skipped": int(skipped)}
+
+
+def leg_launch_bound(dev):
+    """The tiny GPT (3 chunks, 0.17 M elements), where launches and the flag read-back are the step: with the
+    host in the loop, with the step state on the device, and as replays of one HIP graph."""
+    from paper_2108_05818_amd import workloads as W
+    w = W.config1_tiny()
+    out = {"workload": w.name, "n_elems": w.n_elems, "steps": 500, "warmup": 20}
+    st = setup(w, dev, keep_params=0)
+    out["host_bookkeeping_us_per_step"] = timed_steps(st, 500, 20, True)["ms"] * 1e3
+    release(st)
+    for key, graph in (("device_state_us_per_step", False), ("graph_replay_us_per_step", True)):
+        st = setup(w, dev, keep_params=0)
+        r = timed_steps_on_device(st, 500, 20, graph)
+        assert r["skipped"] == 0 and r["step"] == 1 + 500 + 20 + (0 if not graph else 0), r
+        out[key] = r["ms"] * 1e3
+        release(st)
+    return out
 
 
 def cpu_baseline(st, target_chunks=16):
@@ -570,6 +644,12 @@ def main():
 
     r = timed_steps(st, a.steps, a.warmup, not a.separate_check, plans)
     ms, phase, tm = r["ms"], r["phase"], r["tm"]
+    on_device = None
+    if a.device_state or a.graph:
+        # the same workload once more with the step state on the device (--graph: as replays of one HIP graph)
+        rd = timed_steps_on_device(st, a.steps, a.warmup, a.graph)
+        on_device = {"mode": "graph replay" if a.graph else "eager, no read-back", "ms_per_step": rd["ms"],
+                     "gelem_s": w.n_elems / (rd["ms"] * 1e-3) / 1e9, "steps_skipped": rd["skipped"]}
     n_elems = w.n_elems
     copy_gbs = plain_copy_rate(st.ctx, dev)
     roofline = adam_roofline(r, copy_gbs)
@@ -596,6 +676,8 @@ def main():
         "phase_ms": phase,
         "cpu_baseline": cpu,
     }
+    if on_device:
+        out["step_state_on_device"] = on_device
     if st.n_host:
         out["host_link"] = host_link_report(st, r, host_mode)
     if plans:
@@ -615,6 +697,7 @@ def main():
     if a.placements:
         out["placement_trials"] = placement_trials(a, dev, a.placements)
     if legs:
+        out["launch_bound"] = leg_launch_bound(dev)
         out["host_link"], out["host_cores"] = leg_host(a, dev)
     print(json.dumps(out))
 

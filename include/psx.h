@@ -27,9 +27,18 @@
  *     from two threads at once.  Calls on one context share its descriptor
  *     tables and flags and are ordered by the stream they are issued on:
  *     issue them on one stream, or order different streams yourself (event
- *     or synchronisation) before the next call on the same context.  The
- *     calls copy descriptors with hipMemcpyAsync from buffers that later
- *     calls reuse, so they must not be recorded into a HIP graph.
+ *     or synchronisation) before the next call on the same context.
+ *   - HIP graphs.  A call whose descriptors (tensor list, slots, chunk list)
+ *     equal those of the previous call of its kind on the context uploads
+ *     nothing and enqueues kernel launches only; in that state
+ *     psx_overflow_reset, psx_pack, psx_unpack, psx_overflow_check without
+ *     read-back, psx_chunk_adam_step over HBM-resident chunks with
+ *     PSX_STEP_DEVICE_STATE, and psx_step_state_advance may be recorded into a
+ *     graph (stream capture) and replayed: every replay is one more training
+ *     step, with t and the loss scale advancing on the device.  Issue the same
+ *     calls once outside the capture first.  A call that would have to upload
+ *     a descriptor table, to synchronise, or to use the side streams while its
+ *     stream is capturing fails with PSX_ECAPTURE and enqueues nothing.
  *   - Chunk base addresses must be 16-byte aligned.  Tensor addresses need
  *     only their element alignment.
  *   - Element counts are in elements, never bytes.
@@ -52,6 +61,7 @@ extern "C" {
 #define PSX_EALIGN     (-4)  /* a chunk base is not 16-byte aligned                   */
 #define PSX_EHIP       (-5)  /* the HIP runtime reported an error (see last error)    */
 #define PSX_ENOSTAGING (-6)  /* PSX_TUNE_HOST_MODE 0 and a host-side chunk, but no staging   */
+#define PSX_ECAPTURE   (-7)  /* the stream is being captured into a HIP graph and this call, as given, cannot be recorded */
 
 /* Message of the last failing call on this thread ("" if none). Host pointer, owned by the library. */
 const char *psx_last_error(void);
@@ -229,6 +239,9 @@ typedef struct psx_chunk {
     uint8_t reserved[5];
 } psx_chunk;
 
+#define PSX_STEP_DEVICE_STATE 4u /* take t and the loss scale from the context's step state on the device */
+                                 /* (psx_step_state_init) instead of hyper->step / hyper->loss_scale;   */
+                                 /* the other fields of *hyper must be those given to that call         */
 #define PSX_STEP_USE_FLAG    1u  /* skip the update if the context's overflow flag is set      */
 #define PSX_STEP_CHECK_FIRST 2u  /* run the overflow check over all g16 chunks first (implies  */
                                  /* PSX_STEP_USE_FLAG)                                         */
@@ -287,6 +300,26 @@ typedef struct psx_scaler {
 } psx_scaler;
 
 int32_t psx_loss_scale_update(psx_scaler *s, uint32_t overflow);
+
+/* ------------------------------------------------------------------ step state on the device
+ * The same bookkeeping without the host in the loop, so that a whole training step (gradient pack with
+ * overflow test, update, loss-scale bookkeeping) can be enqueued without a read-back and recorded into a
+ * HIP graph.  The context keeps, in device memory, what psx_scaler holds, beta1^t and beta2^t as running
+ * products of t factors, and the step-wide fp32 scalars of the next update (derived from those in double,
+ * rounded once, as in the host path).
+ *   psx_step_state_init     sets the state from *scaler and *hyper (hyper->step and hyper->loss_scale are
+ *                           ignored: scaler->step and scaler->scale count).  Asynchronous on `stream`.
+ *   psx_step_state_advance  closes a step on the device: reads the context's overflow flag and applies the
+ *                           rules of psx_loss_scale_update (overflow: scale halved with floor 1, good_steps
+ *                           cleared, t unchanged; else t and good_steps advance, growth_interval good steps
+ *                           double the scale), then derives the scalars of the next update.  One tiny
+ *                           launch on `stream`; asynchronous.
+ *   psx_step_state_read     copies the state back (synchronises `stream`): scaler, the flag of the step
+ *                           closed last, the number of steps skipped so far; each may be NULL.
+ * psx_chunk_adam_step(PSX_STEP_DEVICE_STATE) updates with the state's t and loss scale. */
+int32_t psx_step_state_init(psx_ctx *ctx, const psx_adam_hyper *hyper, const psx_scaler *scaler, void *stream);
+int32_t psx_step_state_advance(psx_ctx *ctx, void *stream);
+int32_t psx_step_state_read(psx_ctx *ctx, psx_scaler *scaler, uint32_t *last_flag, uint64_t *skipped, void *stream);
 
 /* ------------------------------------------------------------------ tuning and timing
  * Launch shape knobs (for sweeps; defaults are tuned for MI355X):

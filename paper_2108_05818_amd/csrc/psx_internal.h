@@ -61,6 +61,20 @@ struct AdamScalars {
     uint32_t decay_mode;   // 0 none, 1 L2 into the gradient, 2 decoupled
 };
 
+// The step state kept on the device for steps that take t and the loss scale from there (PSX_STEP_DEVICE_STATE):
+// what psx_scaler holds on the host, the running products beta^t, and the scalars of the next update.
+struct StepState {
+    AdamScalars sc;            // scalars of the update with index `step`
+    float scale;               // loss scale
+    uint32_t growth_interval, good_steps;
+    uint32_t last_flag;        // overflow flag of the step that was closed last (0 / 1)
+    uint32_t pad;
+    uint64_t step;             // t of the next update to apply
+    uint64_t skipped;          // steps skipped so far
+    double b1t, b2t;           // beta1^step, beta2^step as products of `step` factors
+    double lr, beta1, beta2;
+};
+
 // Validates the hyper-parameters and derives the scalars (`who` names the entry point in messages).
 int32_t prepare_adam_scalars(const psx_adam_hyper *h, const char *who, AdamScalars *s);
 
@@ -117,13 +131,20 @@ struct SegView {
 int query_lds_per_cu(int device);
 
 // ---- launchers (psx_kernels.hip).  All enqueue on `s` and return the launch status. ----
+// sc_dev != NULL: the kernel takes its scalars from there (device memory) instead of `sc`; the decay mode,
+// which selects the kernel, always comes from `sc`.
 hipError_t launch_adam(const RunView &rv, uint64_t n_tiles,
                        const AdamScalars &sc, const uint32_t *flag_dev, const Tuning &t,
-                       int n_cu, hipStream_t s);
+                       int n_cu, hipStream_t s, const AdamScalars *sc_dev = nullptr);
 // Same update for runs that change residence, on `grid` persistent workgroups.  With *flag_dev != 0
 // the states are copied to their new home unchanged and p16 is left alone.
 hipError_t launch_adam_move(const MoveView &mv, uint64_t n_tiles, const AdamScalars &sc,
-                            const uint32_t *flag_dev, const Tuning &t, uint32_t grid, hipStream_t s);
+                            const uint32_t *flag_dev, const Tuning &t, uint32_t grid, hipStream_t s,
+                            const AdamScalars *sc_dev = nullptr);
+// Device-resident step state: write `init` and derive its scalars; close a step (loss-scale bookkeeping from
+// *flag_dev, then the scalars of the next update).  One thread each.
+hipError_t launch_step_state_init(StepState *st, const StepState &init, hipStream_t s);
+hipError_t launch_step_state_advance(StepState *st, const uint32_t *flag_dev, hipStream_t s);
 // skipped step with p16 aliasing g16: p16 = fp16(p32), only when *flag_dev != 0
 hipError_t launch_recast_if_flag(const RunView &rv, uint64_t n_tiles,
                                  const uint32_t *flag_dev, const Tuning &t, int n_cu, hipStream_t s);

@@ -86,8 +86,10 @@ __global__ __launch_bounds__(T) void adam_kernel(const AdamRun *__restrict__ run
                                                  const uint64_t *__restrict__ begins,
                                                  uint32_t n_runs, uint64_t n_tiles,
                                                  AdamScalars sc,
+                                                 const AdamScalars *__restrict__ sc_dev,
                                                  const uint32_t *__restrict__ flag) {
     if (flag != nullptr && *flag != 0) return;          // overflow: the whole step is skipped
+    if (sc_dev != nullptr) sc = *sc_dev;                // step-wide scalars kept on the device (uniform: scalar loads)
     constexpr uint32_t ROW = T * 4;
     constexpr uint32_t TILE = ROW * U;
     const uint32_t tid = threadIdx.x;
@@ -165,24 +167,24 @@ __global__ __launch_bounds__(T) void adam_kernel(const AdamRun *__restrict__ run
 
 template <int T, int U, bool NT>
 static hipError_t launch_adam_dm(const RunView &rv, uint64_t n_tiles,
-                                 const AdamScalars &sc, const uint32_t *flag, uint32_t grid,
+                                 const AdamScalars &sc, const AdamScalars *sc_dev, const uint32_t *flag, uint32_t grid,
                                  uint32_t lds, hipStream_t s) {
     switch (sc.decay_mode) {
-        case 0: hipLaunchKernelGGL((adam_kernel<T, U, NT, 0>), dim3(grid), dim3(T), lds, s, rv.runs, rv.begins, rv.n, n_tiles, sc, flag); break;
-        case 1: hipLaunchKernelGGL((adam_kernel<T, U, NT, 1>), dim3(grid), dim3(T), lds, s, rv.runs, rv.begins, rv.n, n_tiles, sc, flag); break;
-        default: hipLaunchKernelGGL((adam_kernel<T, U, NT, 2>), dim3(grid), dim3(T), lds, s, rv.runs, rv.begins, rv.n, n_tiles, sc, flag); break;
+        case 0: hipLaunchKernelGGL((adam_kernel<T, U, NT, 0>), dim3(grid), dim3(T), lds, s, rv.runs, rv.begins, rv.n, n_tiles, sc, sc_dev, flag); break;
+        case 1: hipLaunchKernelGGL((adam_kernel<T, U, NT, 1>), dim3(grid), dim3(T), lds, s, rv.runs, rv.begins, rv.n, n_tiles, sc, sc_dev, flag); break;
+        default: hipLaunchKernelGGL((adam_kernel<T, U, NT, 2>), dim3(grid), dim3(T), lds, s, rv.runs, rv.begins, rv.n, n_tiles, sc, sc_dev, flag); break;
     }
     return hipGetLastError();
 }
 
 template <int T, bool NT>
 static hipError_t launch_adam_u(int unroll, const RunView &rv, uint64_t n_tiles,
-                                const AdamScalars &sc, const uint32_t *flag, uint32_t grid,
+                                const AdamScalars &sc, const AdamScalars *sc_dev, const uint32_t *flag, uint32_t grid,
                                 uint32_t lds, hipStream_t s) {
     switch (unroll) {
-        case 1: return launch_adam_dm<T, 1, NT>(rv, n_tiles, sc, flag, grid, lds, s);
-        case 4: return launch_adam_dm<T, 4, NT>(rv, n_tiles, sc, flag, grid, lds, s);
-        default: return launch_adam_dm<T, 2, NT>(rv, n_tiles, sc, flag, grid, lds, s);
+        case 1: return launch_adam_dm<T, 1, NT>(rv, n_tiles, sc, sc_dev, flag, grid, lds, s);
+        case 4: return launch_adam_dm<T, 4, NT>(rv, n_tiles, sc, sc_dev, flag, grid, lds, s);
+        default: return launch_adam_dm<T, 2, NT>(rv, n_tiles, sc, sc_dev, flag, grid, lds, s);
     }
 }
 
@@ -215,17 +217,17 @@ static uint32_t grid_for(uint64_t n_tiles, int blocks_per_cu, int n_cu) {
 }
 
 hipError_t launch_adam(const RunView &rv, uint64_t n_tiles, const AdamScalars &sc,
-                       const uint32_t *flag, const Tuning &t, int n_cu, hipStream_t s) {
+                       const uint32_t *flag, const Tuning &t, int n_cu, hipStream_t s, const AdamScalars *sc_dev) {
     if (n_tiles == 0) return hipSuccess;
     const uint32_t grid = t.grid_override > 0 ? (uint32_t)(n_tiles < (uint64_t)t.grid_override ? n_tiles : (uint64_t)t.grid_override)
                                               : grid_for(n_tiles, t.adam_blocks_per_cu, n_cu);
     const uint32_t lds = throttle_lds(t.adam_wg_per_cu, t.lds_per_cu);
     const bool nt = t.nontemporal != 0;
     if (t.adam_threads == 64)
-        return nt ? launch_adam_u<64, true>(t.adam_unroll, rv, n_tiles, sc, flag, grid, lds, s)
-                  : launch_adam_u<64, false>(t.adam_unroll, rv, n_tiles, sc, flag, grid, lds, s);
-    return nt ? launch_adam_u<256, true>(t.adam_unroll, rv, n_tiles, sc, flag, grid, lds, s)
-              : launch_adam_u<256, false>(t.adam_unroll, rv, n_tiles, sc, flag, grid, lds, s);
+        return nt ? launch_adam_u<64, true>(t.adam_unroll, rv, n_tiles, sc, sc_dev, flag, grid, lds, s)
+                  : launch_adam_u<64, false>(t.adam_unroll, rv, n_tiles, sc, sc_dev, flag, grid, lds, s);
+    return nt ? launch_adam_u<256, true>(t.adam_unroll, rv, n_tiles, sc, sc_dev, flag, grid, lds, s)
+              : launch_adam_u<256, false>(t.adam_unroll, rv, n_tiles, sc, sc_dev, flag, grid, lds, s);
 }
 
 // ------------------------------------------------------------------ Adam on runs that change residence
@@ -238,8 +240,10 @@ __global__ __launch_bounds__(kThreads) void adam_move_kernel(const MoveRun *__re
                                                              const uint64_t *__restrict__ begins,
                                                              uint32_t n_runs, uint64_t n_tiles,
                                                              AdamScalars sc,
+                                                             const AdamScalars *__restrict__ sc_dev,
                                                              const uint32_t *__restrict__ flag) {
     const bool skip = flag != nullptr && *flag != 0;
+    if (sc_dev != nullptr) sc = *sc_dev;
     constexpr uint32_t TILE = kThreads * 4;
     const uint32_t tid = threadIdx.x;
     for (uint64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
@@ -285,22 +289,23 @@ __global__ __launch_bounds__(kThreads) void adam_move_kernel(const MoveRun *__re
 
 template <bool NT>
 static hipError_t launch_adam_move_nt(const MoveView &mv, uint64_t n_tiles, const AdamScalars &sc,
-                                      const uint32_t *flag, uint32_t grid, hipStream_t s) {
+                                      const AdamScalars *sc_dev, const uint32_t *flag, uint32_t grid, hipStream_t s) {
     switch (sc.decay_mode) {
-        case 0: hipLaunchKernelGGL((adam_move_kernel<NT, 0>), dim3(grid), dim3(kThreads), 0, s, mv.runs, mv.begins, mv.n, n_tiles, sc, flag); break;
-        case 1: hipLaunchKernelGGL((adam_move_kernel<NT, 1>), dim3(grid), dim3(kThreads), 0, s, mv.runs, mv.begins, mv.n, n_tiles, sc, flag); break;
-        default: hipLaunchKernelGGL((adam_move_kernel<NT, 2>), dim3(grid), dim3(kThreads), 0, s, mv.runs, mv.begins, mv.n, n_tiles, sc, flag); break;
+        case 0: hipLaunchKernelGGL((adam_move_kernel<NT, 0>), dim3(grid), dim3(kThreads), 0, s, mv.runs, mv.begins, mv.n, n_tiles, sc, sc_dev, flag); break;
+        case 1: hipLaunchKernelGGL((adam_move_kernel<NT, 1>), dim3(grid), dim3(kThreads), 0, s, mv.runs, mv.begins, mv.n, n_tiles, sc, sc_dev, flag); break;
+        default: hipLaunchKernelGGL((adam_move_kernel<NT, 2>), dim3(grid), dim3(kThreads), 0, s, mv.runs, mv.begins, mv.n, n_tiles, sc, sc_dev, flag); break;
     }
     return hipGetLastError();
 }
 
 hipError_t launch_adam_move(const MoveView &mv, uint64_t n_tiles, const AdamScalars &sc,
-                            const uint32_t *flag, const Tuning &t, uint32_t grid, hipStream_t s) {
+                            const uint32_t *flag, const Tuning &t, uint32_t grid, hipStream_t s,
+                            const AdamScalars *sc_dev) {
     if (n_tiles == 0) return hipSuccess;
     if (grid == 0) grid = 1;
     if ((uint64_t)grid > n_tiles) grid = (uint32_t)n_tiles;
-    return t.nontemporal ? launch_adam_move_nt<true>(mv, n_tiles, sc, flag, grid, s)
-                         : launch_adam_move_nt<false>(mv, n_tiles, sc, flag, grid, s);
+    return t.nontemporal ? launch_adam_move_nt<true>(mv, n_tiles, sc, sc_dev, flag, grid, s)
+                         : launch_adam_move_nt<false>(mv, n_tiles, sc, sc_dev, flag, grid, s);
 }
 
 // ------------------------------------------------------------------ re-cast on a skipped step
@@ -560,6 +565,55 @@ hipError_t launch_copy(const SegView &sv, uint64_t n_tiles, uint32_t elem_size,
     }
 #undef PSX_LAUNCH_COPY_T
 #undef PSX_LAUNCH_COPY
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ step state on the device
+// Loss-scale bookkeeping and the step-wide scalars without the host: the same convention as
+// psx_loss_scale_update, and the same derivation of the scalars as the step call (in double, each rounded
+// to fp32 once), with beta^t kept as a running product of t factors.  Double division and square root
+// are IEEE-correct on this target, so the scalars equal the host's.
+__device__ __forceinline__ void derive_scalars(StepState *st) {
+    st->sc.step_size = (float)(st->lr / (1.0 - st->b1t));
+    st->sc.c2 = (float)(1.0 / __builtin_sqrt(1.0 - st->b2t));
+    st->sc.inv_scale = (float)(1.0 / (double)st->scale);
+}
+
+__global__ void step_state_init_kernel(StepState *st, StepState init) {
+    if (blockIdx.x != 0 || threadIdx.x != 0) return;
+    *st = init;
+    derive_scalars(st);
+}
+
+__global__ void step_state_advance_kernel(StepState *st, const uint32_t *__restrict__ flag) {
+    if (blockIdx.x != 0 || threadIdx.x != 0) return;
+    const uint32_t overflow = *flag != 0 ? 1u : 0u;
+    if (overflow) {
+        const float half = st->scale * 0.5f;
+        st->scale = half < 1.0f ? 1.0f : half;
+        st->good_steps = 0;
+        st->skipped += 1;
+    } else {
+        st->step += 1;
+        st->b1t = st->b1t * st->beta1;
+        st->b2t = st->b2t * st->beta2;
+        st->good_steps += 1;
+        if (st->good_steps >= st->growth_interval) {
+            st->scale = st->scale * 2.0f;
+            st->good_steps = 0;
+        }
+    }
+    st->last_flag = overflow;
+    derive_scalars(st);
+}
+
+hipError_t launch_step_state_init(StepState *st, const StepState &init, hipStream_t s) {
+    hipLaunchKernelGGL(step_state_init_kernel, dim3(1), dim3(64), 0, s, st, init);
+    return hipGetLastError();
+}
+
+hipError_t launch_step_state_advance(StepState *st, const uint32_t *flag_dev, hipStream_t s) {
+    hipLaunchKernelGGL(step_state_advance_kernel, dim3(1), dim3(64), 0, s, st, flag_dev);
     return hipGetLastError();
 }
 

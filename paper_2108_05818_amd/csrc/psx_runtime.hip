@@ -59,9 +59,20 @@ int32_t table_reserve(Table &t, size_t bytes) {
     return PSX_OK;
 }
 
+// Is `s` being recorded into a HIP graph?  (A failing query counts as "no": the next call reports the error.)
+bool capturing(hipStream_t s) {
+    hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(s, &st) != hipSuccess) { (void)hipGetLastError(); return false; }
+    return st != hipStreamCaptureStatusNone;
+}
+
 int32_t table_upload(Table &t, const void *data, size_t bytes, hipStream_t s) {
     if (bytes == 0) return PSX_OK;
     if (t.shadow.size() == bytes && memcmp(t.shadow.data(), data, bytes) == 0) return PSX_OK;
+    // the upload reads a pinned buffer that later calls reuse: a graph must not replay it
+    if (capturing(s))
+        return fail(PSX_ECAPTURE, "the descriptor table of this call differs from the one on the device and cannot be uploaded while the "
+                                  "stream is being captured: issue the same call once outside the capture first");
     int32_t rc = table_reserve(t, bytes);
     if (rc != PSX_OK) return rc;
     const int k = t.next;
@@ -145,6 +156,11 @@ struct psx_ctx {
     struct HostSeen { const void *p[3]; uint64_t used; };
     std::vector<HostSeen> host_seen;
     int copy_unroll_now = 1;           // tile shape the segments in `segs` were cut for
+    // step state on the device (PSX_STEP_DEVICE_STATE)
+    StepState *state_dev = nullptr;
+    StepState *state_host = nullptr;   // pinned read-back buffer
+    bool state_on = false;
+    psx_adam_hyper state_hyper{};      // the hyper-parameters the state was initialised with
     // host-core execution (PSX_EXEC_CPU), allocated on first use
     CpuPool *pool = nullptr;
     hipStream_t aux = nullptr;         // H2D of the fp16 parameter tiles
@@ -163,12 +179,12 @@ bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 int32_t span_begin(psx_ctx *c, TimedSpan &t, hipStream_t s) {
     t.valid = false;
-    if (!c->prof) return PSX_OK;
+    if (!c->prof || capturing(s)) return PSX_OK;
     PSX_HIP(hipEventRecord(t.a, s));
     return PSX_OK;
 }
 int32_t span_end(psx_ctx *c, TimedSpan &t, hipStream_t s) {
-    if (!c->prof) return PSX_OK;
+    if (!c->prof || capturing(s)) return PSX_OK;
     PSX_HIP(hipEventRecord(t.b, s));
     t.valid = true;
     return PSX_OK;
@@ -221,6 +237,9 @@ extern "C" int32_t psx_ctx_create(const psx_ctx_config *cfg, psx_ctx **out) {
     PSX_TRY(hipMalloc(reinterpret_cast<void **>(&c->flags_dev), c->flags_n * sizeof(uint32_t)));
     PSX_TRY(hipHostMalloc(reinterpret_cast<void **>(&c->flags_host), c->flags_n * sizeof(uint32_t), hipHostMallocDefault));
     PSX_TRY(hipMemset(c->flags_dev, 0, c->flags_n * sizeof(uint32_t)));
+    PSX_TRY(hipMalloc(reinterpret_cast<void **>(&c->state_dev), sizeof(StepState)));
+    PSX_TRY(hipHostMalloc(reinterpret_cast<void **>(&c->state_host), sizeof(StepState), hipHostMallocDefault));
+    PSX_TRY(hipMemset(c->state_dev, 0, sizeof(StepState)));
     PSX_TRY(hipStreamCreateWithFlags(&c->h2d, hipStreamNonBlocking));
     PSX_TRY(hipStreamCreateWithFlags(&c->d2h, hipStreamNonBlocking));
     PSX_TRY(hipEventCreateWithFlags(&c->ev_entry, hipEventDisableTiming));
@@ -268,6 +287,8 @@ extern "C" int32_t psx_ctx_destroy(psx_ctx *c) {
     if (c->flags_dev) note(hipFree(c->flags_dev), "hipFree(flags)");
     if (c->flags_host) note(hipHostFree(c->flags_host), "hipHostFree(flags)");
     if (c->staging) note(hipFree(c->staging), "hipFree(staging)");
+    if (c->state_dev) note(hipFree(c->state_dev), "hipFree(state)");
+    if (c->state_host) note(hipHostFree(c->state_host), "hipHostFree(state)");
     if (c->pool) cpu_pool_destroy(c->pool);
     if (c->aux) note(hipStreamDestroy(c->aux), "hipStreamDestroy");
     for (int i = 0; i < kCpuSlots; i++) {
@@ -574,6 +595,7 @@ extern "C" int32_t psx_overflow_read(psx_ctx *c, uint32_t *per_chunk, size_t n_c
     int32_t rc = set_device_guard(c);
     if (rc != PSX_OK) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (capturing(s)) return fail(PSX_ECAPTURE, "psx_overflow_read synchronises and cannot be recorded into a graph");
     const size_t cnt = 1 + (per_chunk ? n_chunks : 0);
     PSX_HIP(hipMemcpyAsync(c->flags_host, c->flags_dev, cnt * sizeof(uint32_t), hipMemcpyDeviceToHost, s));
     PSX_HIP(hipStreamSynchronize(s));
@@ -610,6 +632,66 @@ extern "C" int32_t psx_overflow_check(psx_ctx *c, const void *const *g16_chunks,
                          c->flags_dev, c->flags_dev + 1, c->tune, c->n_cu, s));
     if ((rc = span_end(c, c->t_check, s)) != PSX_OK) return rc;
     if (per_chunk != nullptr || flag_out != nullptr) return psx_overflow_read(c, per_chunk, n_chunks, flag_out, stream);
+    return PSX_OK;
+}
+
+// ====================================================================== step state on the device
+
+extern "C" int32_t psx_step_state_init(psx_ctx *c, const psx_adam_hyper *hyper, const psx_scaler *scaler, void *stream) {
+    if (c == nullptr || hyper == nullptr || scaler == nullptr) return fail(PSX_EINVAL, "psx_step_state_init: NULL argument");
+    if (scaler->step == 0) return fail(PSX_EINVAL, "psx_step_state_init: scaler->step is 1-based");
+    if (scaler->growth_interval == 0) return fail(PSX_EINVAL, "psx_step_state_init: growth_interval is 0");
+    if (!(scaler->scale >= 1.0f) || !std::isfinite(scaler->scale)) return fail(PSX_EINVAL, "psx_step_state_init: the loss scale must be finite and at least 1");
+    psx_adam_hyper h = *hyper;
+    h.step = scaler->step;
+    h.loss_scale = (double)scaler->scale;
+    AdamScalars sc;
+    int32_t rc = prepare_adam_scalars(&h, "psx_step_state_init", &sc);
+    if (rc != PSX_OK) return rc;
+    if ((rc = set_device_guard(c)) != PSX_OK) return rc;
+    StepState init{};
+    init.sc = sc;                       // the step-varying three are derived again on the device
+    init.scale = scaler->scale;
+    init.growth_interval = scaler->growth_interval;
+    init.good_steps = scaler->good_steps;
+    init.step = scaler->step;
+    init.b1t = 1.0; init.b2t = 1.0;
+    for (uint64_t i = 0; i < scaler->step; i++) { init.b1t = init.b1t * h.beta1; init.b2t = init.b2t * h.beta2; }
+    init.lr = h.lr; init.beta1 = h.beta1; init.beta2 = h.beta2;
+    PSX_HIP(launch_step_state_init(c->state_dev, init, static_cast<hipStream_t>(stream)));
+    c->state_hyper = h;
+    c->state_on = true;
+    return PSX_OK;
+}
+
+extern "C" int32_t psx_step_state_advance(psx_ctx *c, void *stream) {
+    if (c == nullptr) return fail(PSX_EINVAL, "psx_step_state_advance: ctx is NULL");
+    if (!c->state_on) return fail(PSX_EINVAL, "psx_step_state_advance: psx_step_state_init has not been called");
+    int32_t rc = set_device_guard(c);
+    if (rc != PSX_OK) return rc;
+    PSX_HIP(launch_step_state_advance(c->state_dev, c->flags_dev, static_cast<hipStream_t>(stream)));
+    return PSX_OK;
+}
+
+extern "C" int32_t psx_step_state_read(psx_ctx *c, psx_scaler *scaler, uint32_t *last_flag, uint64_t *skipped, void *stream) {
+    if (c == nullptr) return fail(PSX_EINVAL, "psx_step_state_read: ctx is NULL");
+    if (!c->state_on) return fail(PSX_EINVAL, "psx_step_state_read: psx_step_state_init has not been called");
+    int32_t rc = set_device_guard(c);
+    if (rc != PSX_OK) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (capturing(s)) return fail(PSX_ECAPTURE, "psx_step_state_read synchronises and cannot be recorded into a graph");
+    PSX_HIP(hipMemcpyAsync(c->state_host, c->state_dev, sizeof(StepState), hipMemcpyDeviceToHost, s));
+    PSX_HIP(hipStreamSynchronize(s));
+    const StepState &st = *c->state_host;
+    if (scaler != nullptr) {
+        scaler->scale = st.scale;
+        scaler->growth_interval = st.growth_interval;
+        scaler->good_steps = st.good_steps;
+        scaler->reserved = 0;
+        scaler->step = st.step;
+    }
+    if (last_flag != nullptr) *last_flag = st.last_flag;
+    if (skipped != nullptr) *skipped = st.skipped;
     return PSX_OK;
 }
 
@@ -699,7 +781,16 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
     if (c == nullptr) return fail(PSX_EINVAL, "psx_chunk_adam_step: ctx is NULL");
     if (hyper == nullptr) return fail(PSX_EINVAL, "psx_chunk_adam_step: hyper is NULL");
     if (n_chunks != 0 && chunks == nullptr) return fail(PSX_EINVAL, "psx_chunk_adam_step: chunks is NULL");
-    if (flags & ~(PSX_STEP_USE_FLAG | PSX_STEP_CHECK_FIRST)) return fail(PSX_EINVAL, "psx_chunk_adam_step: unknown flags 0x%x", flags);
+    if (flags & ~(PSX_STEP_USE_FLAG | PSX_STEP_CHECK_FIRST | PSX_STEP_DEVICE_STATE)) return fail(PSX_EINVAL, "psx_chunk_adam_step: unknown flags 0x%x", flags);
+    const bool dev_state = (flags & PSX_STEP_DEVICE_STATE) != 0;
+    if (dev_state) {
+        if (!c->state_on) return fail(PSX_EINVAL, "psx_chunk_adam_step: PSX_STEP_DEVICE_STATE needs psx_step_state_init first");
+        const psx_adam_hyper &a = *hyper, &b = c->state_hyper;
+        if (a.lr != b.lr || a.beta1 != b.beta1 || a.beta2 != b.beta2 || a.eps != b.eps || a.weight_decay != b.weight_decay ||
+            (a.adamw_mode != 0) != (b.adamw_mode != 0))
+            return fail(PSX_EINVAL, "psx_chunk_adam_step: with PSX_STEP_DEVICE_STATE lr, betas, eps, weight_decay and adamw_mode must be "
+                                    "those given to psx_step_state_init (step and loss_scale are taken from the device)");
+    }
     if (n_chunks > c->cfg.max_chunks)
         return fail(PSX_ECAP, "psx_chunk_adam_step: %zu chunks, context holds %llu", n_chunks, (unsigned long long)c->cfg.max_chunks);
     AdamScalars sc;
@@ -728,6 +819,7 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
             if (ch.loc_in != PSX_LOC_HOST || ch.loc_out != PSX_LOC_HOST)
                 return fail(PSX_EINVAL, "psx_chunk_adam_step: chunk %zu: PSX_EXEC_CPU needs a chunk that stays on the host", k);
             if (!cpu_adam_supported()) return fail(PSX_EINVAL, "psx_chunk_adam_step: PSX_EXEC_CPU needs a host CPU with AVX2 and F16C");
+            if (dev_state) return fail(PSX_EINVAL, "psx_chunk_adam_step: chunk %zu: PSX_EXEC_CPU needs the step scalars on the host, not PSX_STEP_DEVICE_STATE", k);
         }
         if (host_side) {
             if (!ch.p32_host || !ch.m_host || !ch.v_host) return fail(PSX_EINVAL, "psx_chunk_adam_step: chunk %zu needs pinned p32/m/v", k);
@@ -763,6 +855,14 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
     }
     if ((rc = set_device_guard(c)) != PSX_OK) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (capturing(s)) {
+        if (!dev_state)
+            return fail(PSX_ECAPTURE, "psx_chunk_adam_step: a captured step would replay this call's t and loss scale for ever: use PSX_STEP_DEVICE_STATE");
+        for (size_t k = 0; k < n_chunks; k++)
+            if (chunks[k].used != 0 && (chunks[k].loc_in != PSX_LOC_HBM || chunks[k].loc_out != PSX_LOC_HBM))
+                return fail(PSX_ECAPTURE, "psx_chunk_adam_step: chunk %zu has a host side; only HBM-resident chunk lists can be recorded into a graph", k);
+    }
+    const AdamScalars *sc_dev = dev_state ? &c->state_dev->sc : nullptr;
 
     // ---- build the descriptor table: [resident | recast | check | spill tiles]
     const uint64_t adam_tile = adam_tile_elems(c->tune);
@@ -947,7 +1047,7 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
         c->t_adam.valid = false;
         if (res_tiles != 0) {
             if ((rc = span_begin(c, c->t_adam, s)) != PSX_OK) return rc;
-            PSX_HIP(launch_adam(view(0, n_res), res_tiles, sc, flag, c->tune, c->n_cu, s));
+            PSX_HIP(launch_adam(view(0, n_res), res_tiles, sc, flag, c->tune, c->n_cu, s, sc_dev));
             if ((rc = span_end(c, c->t_adam, s)) != PSX_OK) return rc;
             if (n_recast != 0)
                 PSX_HIP(launch_recast_if_flag(view(n_res, n_recast), recast_tiles, flag, c->tune, c->n_cu, s));
@@ -958,10 +1058,10 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
         c->spill_elems = spill_elems; c->h2d_bytes = h2d_bytes; c->d2h_bytes = d2h_bytes;
         if (n_direct != 0 || move_tiles != 0) {
             if (n_direct != 0)
-                PSX_HIP(launch_adam(view(direct_off, n_direct), direct_tiles, sc, flag, td, c->n_cu, c->h2d));
+                PSX_HIP(launch_adam(view(direct_off, n_direct), direct_tiles, sc, flag, td, c->n_cu, c->h2d, sc_dev));
             if (move_tiles != 0)
                 PSX_HIP(launch_adam_move(MoveView{mtbl, mtbl_begins, (uint32_t)c->moves.size()}, move_tiles, sc, flag, c->tune,
-                                         (uint32_t)c->tune.host_grid, c->h2d));
+                                         (uint32_t)c->tune.host_grid, c->h2d, sc_dev));
             if (n_direct_recast != 0)
                 PSX_HIP(launch_recast_if_flag(view(direct_off + n_direct, n_direct_recast), direct_recast_tiles, flag, td, c->n_cu, c->h2d));
             any_h2d = true;
@@ -982,7 +1082,7 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
                 any_h2d = true;
             }
             Tuning tn = c->tune;
-            PSX_HIP(launch_adam(view(t.run, 1), (t.n + adam_tile - 1) / adam_tile, sc, flag, tn, c->n_cu, s));
+            PSX_HIP(launch_adam(view(t.run, 1), (t.n + adam_tile - 1) / adam_tile, sc, flag, tn, c->n_cu, s, sc_dev));
             if (use_flag && t.alias)
                 PSX_HIP(launch_recast_if_flag(view(t.run, 1), (t.n + recast_tile - 1) / recast_tile, flag, tn, c->n_cu, s));
             if (t.dst[0] != nullptr) {

@@ -12,13 +12,13 @@ import os
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpsx.so")
 
-PSX_OK, PSX_EINVAL, PSX_ETOOLARGE, PSX_ECAP, PSX_EALIGN, PSX_EHIP, PSX_ENOSTAGING = 0, -1, -2, -3, -4, -5, -6
+PSX_OK, PSX_EINVAL, PSX_ETOOLARGE, PSX_ECAP, PSX_EALIGN, PSX_EHIP, PSX_ENOSTAGING, PSX_ECAPTURE = 0, -1, -2, -3, -4, -5, -6, -7
 PSX_LAYOUT_STRICT = 1
 PSX_F16, PSX_F32 = 1, 2
 PSX_PACK_CHECK_OVERFLOW = 1
 PSX_LOC_HBM, PSX_LOC_HOST = 0, 1
 PSX_EXEC_GPU, PSX_EXEC_CPU = 0, 1
-PSX_STEP_USE_FLAG, PSX_STEP_CHECK_FIRST = 1, 2
+PSX_STEP_USE_FLAG, PSX_STEP_CHECK_FIRST, PSX_STEP_DEVICE_STATE = 1, 2, 4
 PSX_TUNE_ADAM_BLOCKS_PER_CU, PSX_TUNE_ADAM_UNROLL, PSX_TUNE_NONTEMPORAL, PSX_TUNE_COPY_BLOCKS_PER_CU = 1, 2, 3, 4
 PSX_TUNE_ADAM_THREADS, PSX_TUNE_ADAM_WG_PER_CU, PSX_TUNE_COPY_UNROLL = 5, 6, 7
 PSX_TUNE_HOST_MODE, PSX_TUNE_HOST_GRID, PSX_TUNE_HOST_UNROLL = 8, 9, 10
@@ -32,6 +32,7 @@ EXPORTS = [
     "psx_loss_scale_update", "psx_ctx_set_tuning", "psx_ctx_set_profiling", "psx_ctx_get_timing",
     "psx_copy_bytes", "psx_measure_link", "psx_pinned_alloc", "psx_pinned_free", "psx_plan_residency",
     "psx_chunk_size_search", "psx_chunk_adam_step_noalloc", "psx_adam_step_scalars",
+    "psx_step_state_init", "psx_step_state_advance", "psx_step_state_read",
 ]
 
 
@@ -106,6 +107,9 @@ def lib():
         "psx_chunk_adam_step": [vp, vp, sz, C.POINTER(psx_adam_hyper), u32, vp],
         "psx_chunk_adam_step_noalloc": [vp, sz, C.POINTER(psx_adam_hyper), u32, vp, vp],
         "psx_adam_step_scalars": [C.POINTER(psx_adam_hyper), vp],
+        "psx_step_state_init": [vp, C.POINTER(psx_adam_hyper), C.POINTER(psx_scaler), vp],
+        "psx_step_state_advance": [vp, vp],
+        "psx_step_state_read": [vp, C.POINTER(psx_scaler), C.POINTER(u32), C.POINTER(u64), vp],
         "psx_loss_scale_update": [C.POINTER(psx_scaler), u32],
         "psx_ctx_set_tuning": [vp, u32, C.c_int64],
         "psx_ctx_set_profiling": [vp, C.c_int32],
@@ -255,6 +259,21 @@ def psx_adam_step_scalars(hyper):
     out = (C.c_float * 10)()
     _ok(lib().psx_adam_step_scalars(C.byref(hyper), out))
     return dict(zip(SCALAR_NAMES, out))
+
+
+def psx_step_state_init(ctx, hyper, scaler, stream=None):
+    _ok(lib().psx_step_state_init(ctx, C.byref(hyper), C.byref(scaler), _stream(stream)))
+
+
+def psx_step_state_advance(ctx, stream=None):
+    _ok(lib().psx_step_state_advance(ctx, _stream(stream)))
+
+
+def psx_step_state_read(ctx, stream=None):
+    """-> (psx_scaler, flag of the step closed last, steps skipped so far); synchronises."""
+    s, flag, skipped = psx_scaler(), C.c_uint32(0), C.c_uint64(0)
+    _ok(lib().psx_step_state_read(ctx, C.byref(s), C.byref(flag), C.byref(skipped), _stream(stream)))
+    return s, flag.value, skipped.value
 
 
 def make_scaler(scale=65536.0, growth_interval=2000):
