@@ -56,9 +56,12 @@ def parse():
     ap.add_argument("--device-state", action="store_true",
                     help="also time the steps with t, the loss scale and the loss-scale bookkeeping on the device (no read-back per step)")
     ap.add_argument("--graph", action="store_true", help="as --device-state, with the step recorded once into a HIP graph and replayed")
+    ap.add_argument("--leg", default="", choices=["", "launch_bound", "ragged_packing", "host", "moving_residency"],
+                    help="run one leg of the default run alone and print its JSON object (what the default run does in child processes)")
     ap.add_argument("--no-legs", action="store_true",
-                    help="default run only: skip the extra legs (chunk reuse on the same workload; GPT-12.6B with "
-                         "40 %% of the chunks host-resident, over the link and on the host cores)")
+                    help="default run only: skip the extra legs (chunk reuse on the same workload; the launch-bound tiny "
+                         "model; ragged packing; GPT-12.6B with 40 %% of the chunks host-resident, over the link and on the "
+                         "host cores; GPT-20B shapes with a moving HBM budget)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="also launch psx_copy_bytes once over this many MiB (a plain copy of known size, "
                          "the yardstick the HBM traffic counters are scaled by)")
@@ -582,6 +585,61 @@ def leg_host(a, dev):
     return link, cores
 
 
+def residency_report(r, w, host_fraction):
+    link = r["link"]
+    moved = link["h2d"] + link["d2h"]
+    floor = link["min_h2d"] + link["min_d2h"]
+    return {"hbm_budget": f"{1.0 - host_fraction:.2f} of the fp32-state chunks, x (1 + {w.budget_jitter} u_t), u_t ~ U(-1, 1) seeded",
+            "resident_chunks_per_step": link["resident_chunks"], "chunks_that_changed_residence": link["moved_chunks"],
+            "link_bytes": moved, "link_bytes_minimum": floor, "link_bytes_over_minimum": moved / floor if floor else None}
+
+
+def leg_ragged(dev):
+    """Config 3: 5000 tensors with log-uniform sizes in 16 Mi chunks; what it stresses is the multi-tensor pack and
+    unpack (segments with arbitrary alignment), the Adam launch is the headline's kernel on another chunk size."""
+    from paper_2108_05818_amd import workloads as W
+    w = W.config3_ragged()
+    st = setup(w, dev, keep_params=0)
+    r = timed_steps(st, 10, 3, True)
+    out = {"workload": w.name, "n_elems": w.n_elems, "n_tensors": len(w.numel), "n_chunks": st.nch, "chunk_elems": w.chunk_elems,
+           "steps": 10, "warmup": 3, "ms_per_step": r["ms"], "gelem_s": w.n_elems / (r["ms"] * 1e-3) / 1e9,
+           "pack_or_unpack_ms": r["phase"]["pack_ms"], "pack_or_unpack_GBs": 4 * w.n_elems / (r["phase"]["pack_ms"] * 1e-3) / 1e9,
+           "roofline": adam_roofline(r)}
+    release(st)
+    return out
+
+
+def leg_moving_residency(a, dev):
+    """Config 5's tensor shapes at 12 layers: the HBM budget moves by +-30 % per step (seeded), psx_plan_residency
+    picks each step's resident set, chunks at its margin change residence while they are updated."""
+    import argparse as _ap
+    b = _ap.Namespace(**vars(a))
+    b.workload, b.layers, b.chunk_elems, b.host_fraction, b.steps, b.warmup = "gpt20b", 0, 0, -1.0, 6, 2
+    w, host_fraction, plans, scaled_from = pick_workload(b)
+    st = setup(w, dev, host_fraction, a.staging_tile, a.staging_slots, keep_params=0, plans=plans)
+    r = timed_steps(st, b.steps, b.warmup, True, plans)
+    out = {"workload": w.name, "scaled_from": scaled_from, "n_elems": w.n_elems, "n_chunks": st.nch, "steps": b.steps, "warmup": b.warmup,
+           "ms_per_step": r["ms"], "gelem_s": w.n_elems / (r["ms"] * 1e-3) / 1e9}
+    hl = host_link_report(st, r, 1)
+    out.update({k: hl[k] for k in ("h2d_GBs", "d2h_GBs", "frac", "frac_of_copies_both_at_once")})
+    out["residency"] = residency_report(r, w, host_fraction)
+    release(st)
+    return out
+
+
+def run_leg(name):
+    """Run one leg as a child process (`bench.py --leg NAME`) and return the JSON object it prints."""
+    import subprocess
+    try:
+        r = subprocess.run([sys.executable, os.path.abspath(__file__), "--leg", name], capture_output=True, text=True, timeout=400)
+        lines = [l for l in r.stdout.splitlines() if l.startswith("{")]
+        if r.returncode != 0 or not lines:
+            return {"error": f"leg {name}: exit status {r.returncode}: {r.stderr.strip()[-400:]}"}
+        return json.loads(lines[-1])
+    except subprocess.TimeoutExpired:
+        return {"error": f"leg {name}: no result within 400 s"}
+
+
 def psx_cpu_ok():
     """PSX_EXEC_CPU needs AVX2 + F16C on the host."""
     try:
@@ -607,6 +665,18 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     dev = "cuda:0"
+    if a.leg:
+        if a.leg == "launch_bound":
+            res = leg_launch_bound(dev)
+        elif a.leg == "ragged_packing":
+            res = leg_ragged(dev)
+        elif a.leg == "host":
+            link, cores = leg_host(a, dev)
+            res = {"host_link": link, "host_cores": cores}
+        else:
+            res = leg_moving_residency(a, dev)
+        print(json.dumps(res))
+        return
     w, host_fraction, plans, scaled_from = pick_workload(a)
     # the default run (headline workload, no overrides) appends the other halves of the metric as legs
     headline = (a.workload == "gpt1b" and not a.layers and not a.chunk_elems and host_fraction == 0
@@ -681,12 +751,7 @@ def main():
     if st.n_host:
         out["host_link"] = host_link_report(st, r, host_mode)
     if plans:
-        link = r["link"]
-        moved = link["h2d"] + link["d2h"]
-        floor = link["min_h2d"] + link["min_d2h"]
-        out["residency"] = {"hbm_budget": f"{1.0 - host_fraction:.2f} of the fp32-state chunks, x (1 + {w.budget_jitter} u_t), u_t ~ U(-1, 1) seeded",
-                            "resident_chunks_per_step": link["resident_chunks"], "chunks_that_changed_residence": link["moved_chunks"],
-                            "link_bytes": moved, "link_bytes_minimum": floor, "link_bytes_over_minimum": moved / floor if floor else None}
+        out["residency"] = residency_report(r, w, host_fraction)
     if a.sweep_wg:
         out["wg_per_cu_sweep"] = sweep_wg(st, [int(x) for x in a.sweep_wg.split(",")])
     if legs:
@@ -697,8 +762,13 @@ def main():
     if a.placements:
         out["placement_trials"] = placement_trials(a, dev, a.placements)
     if legs:
-        out["launch_bound"] = leg_launch_bound(dev)
-        out["host_link"], out["host_cores"] = leg_host(a, dev)
+        # each in a process of its own, started after this one has freed its buffers: a workload set up in a
+        # fresh process gets its chunk lists placed in HBM as a real run would, and 220 GB of GPT-12.6B fit
+        out["launch_bound"] = run_leg("launch_bound")
+        out["ragged_packing"] = run_leg("ragged_packing")
+        host = run_leg("host")
+        out["host_link"], out["host_cores"] = (host.get("host_link"), host.get("host_cores")) if "error" not in host else (host, None)
+        out["moving_residency"] = run_leg("moving_residency")
     print(json.dumps(out))
 
 
