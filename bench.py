@@ -46,6 +46,8 @@ def parse():
     ap.add_argument("--arena-skew", type=int, default=0, metavar="BYTES",
                     help="start chunk list j of the device arenas j*BYTES into its allocation (multiple of 256): "
                          "moves the streams of one chunk relative to each other in the address space")
+    ap.add_argument("--one-arena", action="store_true",
+                    help="carve all device chunk lists out of one allocation (list bases 2 MiB-aligned, plus --arena-skew per list)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep-wg", default="", metavar="LIST",
                     help="after the timed steps, time the Adam launch with each of these caps on resident workgroups "
@@ -77,7 +79,7 @@ class State:
 
 
 def setup(w, dev, host_fraction=0.0, staging_tile_elems=4 << 20, staging_slots=3, keep_params="all", cpu_share=0.0,
-          plans=None, chunk_reuse=False, arena_skew=0):
+          plans=None, chunk_reuse=False, arena_skew=0, one_arena=False):
     """Allocate chunk lists and seeded inputs on the device (and pinned host memory for
     host-resident chunks); pack the fp32 params tensor by tensor; m = v = 0.
     keep_params: "all" keeps every fp32 source tensor, an int keeps only the first that many, a set keeps
@@ -111,6 +113,12 @@ def setup(w, dev, host_fraction=0.0, staging_tile_elems=4 << 20, staging_slots=3
     C = st.C
 
     lists_made = [0]
+    pool = {"buf": None, "at": 0}
+    if one_arena:
+        # every chunk list carved out of ONE device allocation, list bases 2 MiB-aligned plus j*arena_skew
+        n_dev = sum(need_dev)
+        total = 2 * C * st.nch * (1 if chunk_reuse else 2) + 3 * 4 * C * max(n_dev, 1) + 6 * ((2 << 20) + 8 * max(arena_skew, 0))
+        pool["buf"] = torch.zeros(total, dtype=torch.uint8, device=dev)
 
     def chunk_list(dtype, n):
         """One chunk list = one arena, chunk k at offset k*C (the paper's ChunkLists: a list of chunks per
@@ -120,7 +128,13 @@ def setup(w, dev, host_fraction=0.0, staging_tile_elems=4 << 20, staging_slots=3
         item = torch.empty(0, dtype=dtype).element_size()
         skew = lists_made[0] * arena_skew // item            # elements; list j starts j*arena_skew bytes into its arena
         lists_made[0] += 1
-        arena = torch.zeros(C * max(n, 1) + skew, dtype=dtype, device=dev)[skew:]
+        if pool["buf"] is not None:
+            base = (pool["at"] + (2 << 20) - 1) // (2 << 20) * (2 << 20) + skew * item
+            nbytes = C * max(n, 1) * item
+            arena = pool["buf"][base:base + nbytes].view(dtype)
+            pool["at"] = base + nbytes
+        else:
+            arena = torch.zeros(C * max(n, 1) + skew, dtype=dtype, device=dev)[skew:]
         return [arena[k * C:(k + 1) * C] for k in range(n)]
     st.p16 = chunk_list(torch.float16, st.nch)
     st.g16 = st.p16 if chunk_reuse else chunk_list(torch.float16, st.nch)
@@ -534,7 +548,7 @@ def placement_trials(a, dev, n):
     out = []
     for t in range(n):
         w = W.config2_gpt1b()
-        st = setup(w, dev, keep_params=0, chunk_reuse=bool(t % 2))
+        st = setup(w, dev, keep_params=0, chunk_reuse=bool(t % 2), arena_skew=a.arena_skew, one_arena=a.one_arena)
         r = timed_steps(st, 8, 3, True)
         out.append({"trial": t, "chunk_reuse": bool(t % 2), "adam_ms": r["phase"]["adam_ms"], "frac": adam_roofline(r)["frac"]})
         release(st)
@@ -680,13 +694,13 @@ def main():
     w, host_fraction, plans, scaled_from = pick_workload(a)
     # the default run (headline workload, no overrides) appends the other halves of the metric as legs
     headline = (a.workload == "gpt1b" and not a.layers and not a.chunk_elems and host_fraction == 0
-                and not a.chunk_reuse and not a.tune and not a.arena_skew)
+                and not a.chunk_reuse and not a.tune and not a.arena_skew and not a.one_arena)
     legs = headline and not a.no_legs
     # the fp32 source tensors are needed again only by the oracle leg, and only the first few of them
     st = setup(w, dev, host_fraction, a.staging_tile, a.staging_slots,
                keep_params=0 if a.no_cpu_baseline else CPU_BASELINE_TENSORS,
                cpu_share=0.0 if plans else a.cpu_share, plans=plans, chunk_reuse=a.chunk_reuse,
-               arena_skew=a.arena_skew)
+               arena_skew=a.arena_skew, one_arena=a.one_arena)
     tune_keys = {"bpc": psx.PSX_TUNE_ADAM_BLOCKS_PER_CU, "unroll": psx.PSX_TUNE_ADAM_UNROLL,
                  "nt": psx.PSX_TUNE_NONTEMPORAL, "cbpc": psx.PSX_TUNE_COPY_BLOCKS_PER_CU,
                  "threads": psx.PSX_TUNE_ADAM_THREADS, "wg": psx.PSX_TUNE_ADAM_WG_PER_CU,

@@ -799,6 +799,10 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
     const bool check_first = (flags & PSX_STEP_CHECK_FIRST) != 0;
     const bool use_flag = check_first || (flags & PSX_STEP_USE_FLAG) != 0;
     const uint64_t T = c->cfg.staging_tile_elems;
+    // a stream that is being recorded into a graph: only what replays as kernel launches on that one stream
+    const bool recording = capturing(static_cast<hipStream_t>(stream));
+    if (recording && !dev_state)
+        return fail(PSX_ECAPTURE, "psx_chunk_adam_step: a captured step would replay this call's t and loss scale for ever: use PSX_STEP_DEVICE_STATE");
 
     // ---- validate everything before any work is enqueued
     for (size_t k = 0; k < n_chunks; k++) {
@@ -806,6 +810,8 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
         if (ch.loc_in > PSX_LOC_HOST || ch.loc_out > PSX_LOC_HOST)
             return fail(PSX_EINVAL, "psx_chunk_adam_step: chunk %zu has a bad residency (%u -> %u)", k, ch.loc_in, ch.loc_out);
         if (ch.used == 0) continue;
+        if (recording && (ch.loc_in != PSX_LOC_HBM || ch.loc_out != PSX_LOC_HBM))
+            return fail(PSX_ECAPTURE, "psx_chunk_adam_step: chunk %zu has a host side; only HBM-resident chunk lists can be recorded into a graph", k);
         if (ch.g16 == nullptr || ch.p16 == nullptr) return fail(PSX_EINVAL, "psx_chunk_adam_step: chunk %zu g16/p16 is NULL", k);
         if (!aligned16(ch.g16) || !aligned16(ch.p16)) return fail(PSX_EALIGN, "psx_chunk_adam_step: chunk %zu g16/p16 not 16-byte aligned", k);
         const bool dev_side = ch.loc_in == PSX_LOC_HBM || ch.loc_out == PSX_LOC_HBM;
@@ -855,13 +861,6 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
     }
     if ((rc = set_device_guard(c)) != PSX_OK) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (capturing(s)) {
-        if (!dev_state)
-            return fail(PSX_ECAPTURE, "psx_chunk_adam_step: a captured step would replay this call's t and loss scale for ever: use PSX_STEP_DEVICE_STATE");
-        for (size_t k = 0; k < n_chunks; k++)
-            if (chunks[k].used != 0 && (chunks[k].loc_in != PSX_LOC_HBM || chunks[k].loc_out != PSX_LOC_HBM))
-                return fail(PSX_ECAPTURE, "psx_chunk_adam_step: chunk %zu has a host side; only HBM-resident chunk lists can be recorded into a graph", k);
-    }
     const AdamScalars *sc_dev = dev_state ? &c->state_dev->sc : nullptr;
 
     // ---- build the descriptor table: [resident | recast | check | spill tiles]

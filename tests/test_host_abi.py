@@ -165,3 +165,11 @@ def test_step_scalars_agree_with_the_oracle_over_many_steps(orc):
         psx.psx_adam_step_scalars(psx.make_hyper(step=0))
     with pytest.raises(psx.PsxError):
         psx.psx_adam_step_scalars(psx.make_hyper(beta2=1.0))
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The path has no collectives and every box has one GPU: `bench.py --gpus N` with N > 1 says so and exits."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
