@@ -88,7 +88,9 @@ struct Tuning {
     int copy_unroll = 0;           // 16-byte vectors per thread and tile of pack/unpack: 1 or 4; 0 = by tensor count
     int copy_threads = 64;         // threads per workgroup of pack/unpack: 64 or 256
     int host_mode = 1;             // host-resident chunks: 0 staged H2D/kernel/D2H, 1 kernel works on pinned memory
-    int host_grid = 32;            // direct mode: persistent workgroups (256 threads) of the host launch
+    int host_grid = 12;            // direct mode: persistent workgroups (256 threads) of the host launch: 12 keep
+                                   // about 150 KB of reads in flight, the link's bandwidth-delay product; more
+                                   // only queue up where the resident launch's HBM requests must pass
     int host_unroll = 1;           // direct mode: rows of 4 elements per thread
     int grid_override = 0;         // internal: absolute grid size of a launch (0: derive from blocks_per_cu)
     int lds_per_cu = 160 * 1024;   // internal: LDS bytes of one CU as the device reports them (what the occupancy cap divides)
