@@ -330,8 +330,8 @@ int32_t psx_step_state_read(psx_ctx *ctx, psx_scaler *scaler, uint32_t *last_fla
  *   PSX_TUNE_COPY_BLOCKS_PER_CU  same as the first, for pack/unpack/check
  *   PSX_TUNE_ADAM_THREADS        threads per workgroup of the Adam kernel: 64 or 256
  *   PSX_TUNE_ADAM_WG_PER_CU      cap on Adam workgroups resident per CU (0 = none)
- *   PSX_TUNE_COPY_UNROLL         16-byte vectors per thread and tile of pack/unpack: 1 or 4; 0 = 4 when more
- *                                than 1024 tensors are passed, else 1 (default)
+ *   PSX_TUNE_COPY_UNROLL         16-byte vectors per thread and tile of pack/unpack: 1 or 4; 0 = the library's
+ *                                choice (default; 1)
  *   PSX_TUNE_COPY_THREADS        threads per workgroup of pack/unpack: 64 (default) or 256
  *   PSX_TUNE_HOST_MODE           chunks with a host side: 0 = H2D / D2H copies on the copy streams (through
  *                                the context's staging tiles for HOST -> HOST, into / out of the device

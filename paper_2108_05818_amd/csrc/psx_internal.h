@@ -105,10 +105,18 @@ inline uint64_t adam_tile_elems(const Tuning &t) { return (uint64_t)t.adam_threa
 constexpr uint64_t kRecastTileElems = (uint64_t)kThreads * 4u * 2u;
 constexpr uint64_t kMoveTileElems = (uint64_t)kThreads * 4u;
 constexpr uint64_t kCheckTileElems = (uint64_t)kThreads * 8u * 4u;   // 8192 fp16 per tile
-// Small tiles of one wavefront copy fastest (measured: 6.7 TB/s against 6.3 with 256 threads), but every tile
-// pays one owner search; with thousands of tensors the search
-// is deep enough that 4x larger tiles win (measured on the 5000-tensor workload).
-inline int copy_unroll_for(const Tuning &t, size_t n_tensors) { return t.copy_unroll != 0 ? t.copy_unroll : (n_tensors > 1024 ? 4 : 1); }
+// Small tiles of one wavefront copy fastest (measured: 6.7 TB/s against 6.3 with 256 threads).  Every tile pays one
+// owner search; the coarse tile index (SegView::hints) keeps it to a lookup and a step or two even with thousands of
+// tensors, so 1 KiB tiles win there as well (5000-tensor workload: 0.93 ms against 0.99 with 4 KiB tiles).
+inline int copy_unroll_for(const Tuning &t, size_t) { return t.copy_unroll != 0 ? t.copy_unroll : 1; }
+// Tiles of one copy segment (n elements of es bytes written to dst): a first tile of the elements in front
+// of the destination's first 16-byte boundary, if any, then whole tiles from that boundary on.  The copy
+// kernel maps tile indices to elements by the same rule.
+inline uint64_t copy_tiles_of(const void *dst, uint64_t n, uint32_t es, uint64_t tile_elems) {
+    uint64_t a = ((16u - (uint32_t)(reinterpret_cast<uintptr_t>(dst) & 15u)) & 15u) / es;
+    if (a > n) a = n;
+    return (a != 0 ? 1u : 0u) + (n - a + tile_elems - 1) / tile_elems;
+}
 inline uint64_t copy_tile_bytes(const Tuning &t, int unroll) { return (uint64_t)(t.copy_threads == 64 ? 64 : 256) * 16u * (uint64_t)(unroll == 1 ? 1 : 4); }
 
 // A section of a descriptor table on the device: n descriptors and, in a dense array of its own,
@@ -127,7 +135,12 @@ struct SegView {
     const CopySeg *segs;
     const uint64_t *begins;
     uint32_t n;
+    // coarse index over the tiles: hints[t >> shift] = owner of tile (t >> shift) << shift, one entry more
+    // than there are groups (the last holds n - 1), so the owner of t lies in [hints[g], hints[g + 1]]
+    const uint32_t *hints;
+    uint32_t shift;
 };
+constexpr uint32_t kMaxHints = 4096;
 
 // LDS bytes per CU of `device` as the runtime reports them; 160 KiB (gfx950) if it reports nothing usable.
 int query_lds_per_cu(int device);

@@ -60,6 +60,19 @@ __device__ __forceinline__ uint32_t find_owner(const uint64_t *__restrict__ begi
     return lo;
 }
 
+// The same with a coarse index in front: hints[g] is the owner of the first tile of group g = tile >> shift and
+// hints[g + 1] that of the next group's (the last entry is n - 1), so only the few entries between them are searched.
+__device__ __forceinline__ uint32_t find_owner_hinted(const uint64_t *__restrict__ begins, const uint32_t *__restrict__ hints,
+                                                      uint32_t shift, uint64_t tile) {
+    const uint64_t g = tile >> shift;
+    uint32_t lo = hints[g], hi = hints[g + 1] + 1;
+    while (hi - lo > 1) {
+        uint32_t mid = (lo + hi) >> 1;
+        if (begins[mid] <= tile) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
 // ------------------------------------------------------------------ Adam
 
 // One element of the update: the formulas of include/psx.h as they stand there.  Contraction is off
@@ -423,12 +436,11 @@ hipError_t launch_check(const RunView &rv, uint64_t n_tiles, uint32_t *flag,
 }
 
 // ------------------------------------------------------------------ pack / unpack
-// One segment = one contiguous piece of a tensor inside one chunk.  A tile is
-// U x 4 KiB of it.  The destination is brought to 16-byte alignment with a few
-// single-element copies, then written with 16-byte stores; the source is read
-// with 16-byte loads as well: directly when it happens to share that
-// alignment, else as pairs of aligned vectors shifted into place with
-// v_alignbyte (every access is naturally aligned).
+// One segment = one contiguous piece of a tensor inside one chunk.  The destination is written with
+// 16-byte stores wherever 16 bytes of it are wanted (single elements before the first and after the
+// last boundary); the source is read with 16-byte loads as well: directly when it happens to share
+// that alignment, else as pairs of aligned vectors shifted into place with v_alignbyte (every access
+// is naturally aligned).
 template <int ES>
 struct ElemT;
 template <>
@@ -444,9 +456,42 @@ __device__ __forceinline__ uint32_t test_vec(const u32x4 &w) {
         return 0;
 }
 
+// 16 wanted bytes that start `mis` bytes into the aligned vector `lo` and end in the next one, `hi`.
+__device__ __forceinline__ u32x4 shift_pair(const u32x4 &lo, const u32x4 &hi, uint32_t mis) {
+    const uint32_t q = mis >> 2, b = mis & 3u;          // whole words and bytes to drop (uniform per tile)
+    const uint32_t d[9] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3], 0u};
+    u32x4 w;
+    switch (q) {
+        case 0:
+#pragma unroll
+            for (int k = 0; k < 4; k++) w[k] = __builtin_amdgcn_alignbyte(d[k + 1], d[k], b);
+            break;
+        case 1:
+#pragma unroll
+            for (int k = 0; k < 4; k++) w[k] = __builtin_amdgcn_alignbyte(d[k + 2], d[k + 1], b);
+            break;
+        case 2:
+#pragma unroll
+            for (int k = 0; k < 4; k++) w[k] = __builtin_amdgcn_alignbyte(d[k + 3], d[k + 2], b);
+            break;
+        default:
+#pragma unroll
+            for (int k = 0; k < 4; k++) w[k] = __builtin_amdgcn_alignbyte(d[k + 4], d[k + 3], b);
+            break;
+    }
+    return w;
+}
+
+// Tiles of a segment are cut so that the destination of every tile but the first starts on a 16-byte
+// boundary: a segment whose destination is misaligned by `a` elements gets a first tile of just those `a`
+// elements, and tiles of TILE_ELEMS elements after it.  (The host counts tiles by the same rule, see
+// copy_tiles_of.)  Whole tiles then never need element-wise heads or tails: they are copied with U
+// 16-byte loads and stores per lane, straight when the source shares the alignment, else from pairs of
+// aligned source vectors shifted into place; only a segment's first and last tile take the general path.
 template <int ES, bool CHECK, bool NT, int U, int T>
 __global__ __launch_bounds__(T) void copy_kernel(const CopySeg *__restrict__ segs,
                                                         const uint64_t *__restrict__ begins,
+                                                        const uint32_t *__restrict__ hints, uint32_t shift,
                                                         uint32_t n_segs, uint64_t n_tiles,
                                                         uint32_t *flag, uint32_t *per_chunk) {
     typedef typename ElemT<ES>::type E;
@@ -454,10 +499,21 @@ __global__ __launch_bounds__(T) void copy_kernel(const CopySeg *__restrict__ seg
     constexpr uint32_t TILE_ELEMS = TILE_BYTES / ES;
     const uint32_t tid = threadIdx.x;
     for (uint64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-        const uint32_t r = find_owner(begins, n_segs, tile);
-        const uint64_t base = (tile - segs[r].tile_begin) * TILE_ELEMS;
-        const uint64_t left = segs[r].n - base;
-        const uint32_t cnt = left < TILE_ELEMS ? (uint32_t)left : TILE_ELEMS;
+        const uint32_t r = find_owner_hinted(begins, hints, shift, tile);
+        const uint64_t n = segs[r].n;
+        const uint64_t t_in = tile - segs[r].tile_begin;
+        uint64_t a = ((16u - (uint32_t)(reinterpret_cast<uintptr_t>(segs[r].dst) & 15u)) & 15u) / ES;   // elements up to the boundary
+        if (a > n) a = n;
+        uint64_t base;
+        uint32_t cnt;
+        if (a != 0 && t_in == 0) {
+            base = 0;
+            cnt = (uint32_t)a;
+        } else {
+            base = a + (t_in - (a != 0 ? 1u : 0u)) * TILE_ELEMS;
+            const uint64_t left = n - base;
+            cnt = left < TILE_ELEMS ? (uint32_t)left : TILE_ELEMS;
+        }
         const unsigned char *s = static_cast<const unsigned char *>(segs[r].src) + base * ES;
         unsigned char *d = static_cast<unsigned char *>(segs[r].dst) + base * ES;
         const uint32_t nbytes = cnt * ES;
@@ -465,12 +521,26 @@ __global__ __launch_bounds__(T) void copy_kernel(const CopySeg *__restrict__ seg
         uint32_t head = (16u - (uint32_t)(reinterpret_cast<uintptr_t>(d) & 15u)) & 15u;
         if (head > nbytes) head = nbytes;
         const uint32_t mis = (uint32_t)(reinterpret_cast<uintptr_t>(s + head) & 15u);
-        if (head == 0 && mis == 0 && nbytes == TILE_BYTES) {
-            // whole aligned tile: U 16-byte loads in flight per lane, then U stores
+        if (head == 0 && nbytes == TILE_BYTES) {
             u32x4 w[U];
+            if (mis == 0) {
+                // whole aligned tile: U 16-byte loads in flight per lane, then U stores
 #pragma unroll
-            for (int u = 0; u < U; u++)
-                w[u] = ld<NT>(gptr<u32x4>(s) + u * T + tid);
+                for (int u = 0; u < U; u++)
+                    w[u] = ld<NT>(gptr<u32x4>(s) + u * T + tid);
+            } else {
+                // whole tile, source off by `mis` bytes: the two aligned source vectors that cover each
+                // output vector (both hold wanted bytes, so no load leaves the tensor's 16-byte blocks)
+                const PSX_GLOBAL u32x4 *ab = gptr<u32x4>(s - mis);
+                u32x4 lo[U], hi[U];
+#pragma unroll
+                for (int u = 0; u < U; u++) {
+                    lo[u] = ld<NT>(ab + u * T + tid);
+                    hi[u] = ld<NT>(ab + u * T + tid + 1);
+                }
+#pragma unroll
+                for (int u = 0; u < U; u++) w[u] = shift_pair(lo[u], hi[u], mis);
+            }
 #pragma unroll
             for (int u = 0; u < U; u++) {
                 bad |= test_vec<ES, CHECK>(w[u]);
@@ -498,29 +568,9 @@ __global__ __launch_bounds__(T) void copy_kernel(const CopySeg *__restrict__ seg
                 // byte and `hi` the last one, so both loads stay inside 16-byte blocks that contain valid
                 // source bytes (never a page the tensor does not touch).
                 const PSX_GLOBAL u32x4 *ab = gptr<u32x4>(sb - mis);
-                const uint32_t q = mis >> 2, b = mis & 3u;      // whole words and bytes to drop (uniform per tile)
                 for (uint32_t i = tid; i < nvec; i += T) {
                     const u32x4 lo = ab[i], hi = ab[i + 1];
-                    uint32_t d[9] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3], 0u};
-                    u32x4 w;
-                    switch (q) {
-                        case 0:
-#pragma unroll
-                            for (int k = 0; k < 4; k++) w[k] = __builtin_amdgcn_alignbyte(d[k + 1], d[k], b);
-                            break;
-                        case 1:
-#pragma unroll
-                            for (int k = 0; k < 4; k++) w[k] = __builtin_amdgcn_alignbyte(d[k + 2], d[k + 1], b);
-                            break;
-                        case 2:
-#pragma unroll
-                            for (int k = 0; k < 4; k++) w[k] = __builtin_amdgcn_alignbyte(d[k + 3], d[k + 2], b);
-                            break;
-                        default:
-#pragma unroll
-                            for (int k = 0; k < 4; k++) w[k] = __builtin_amdgcn_alignbyte(d[k + 4], d[k + 3], b);
-                            break;
-                    }
+                    const u32x4 w = shift_pair(lo, hi, mis);
                     bad |= test_vec<ES, CHECK>(w);
                     gptr<u32x4>(db)[i] = w;
                 }
@@ -547,10 +597,10 @@ hipError_t launch_copy(const SegView &sv, uint64_t n_tiles, uint32_t elem_size,
     do {                                                                                                      \
         if (t.copy_unroll == 1)                                                                               \
             hipLaunchKernelGGL((copy_kernel<ES, CH, NT_, 1, T_>), dim3(grid), dim3(T_), 0, s, sv.segs,        \
-                               sv.begins, sv.n, n_tiles, flag, per_chunk);                                    \
+                               sv.begins, sv.hints, sv.shift, sv.n, n_tiles, flag, per_chunk);                                    \
         else                                                                                                  \
             hipLaunchKernelGGL((copy_kernel<ES, CH, NT_, 4, T_>), dim3(grid), dim3(T_), 0, s, sv.segs,        \
-                               sv.begins, sv.n, n_tiles, flag, per_chunk);                                    \
+                               sv.begins, sv.hints, sv.shift, sv.n, n_tiles, flag, per_chunk);                                    \
     } while (0)
 #define PSX_LAUNCH_COPY(ES, CH, NT_)                                                                          \
     do {                                                                                                      \

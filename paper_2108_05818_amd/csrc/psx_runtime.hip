@@ -102,6 +102,37 @@ int32_t upload_described(Table &t, const std::vector<D> &v, std::vector<unsigned
     return PSX_OK;
 }
 
+// Copy segments: descriptors, their first tiles, and a coarse index over the tiles (at most kMaxHints groups of
+// 2^shift tiles; hints[g] = the segment that owns the first tile of group g) that narrows the owner search of
+// a tile from log2(n) dependent loads to a lookup and a step or two.
+int32_t upload_segments(Table &t, const std::vector<CopySeg> &v, uint64_t n_tiles, std::vector<unsigned char> &blob,
+                        hipStream_t s, const CopySeg **items, const uint64_t **begins, const uint32_t **hints, uint32_t *shift_out) {
+    uint32_t shift = 0;
+    while (((n_tiles + ((1ull << shift) - 1)) >> shift) > kMaxHints) shift++;
+    const size_t groups = (size_t)((n_tiles + ((1ull << shift) - 1)) >> shift);
+    const size_t nd = v.size() * sizeof(CopySeg), nb = v.size() * sizeof(uint64_t);
+    blob.resize(nd + nb + (groups + 1) * sizeof(uint32_t));
+    if (!v.empty()) memcpy(blob.data(), v.data(), nd);
+    uint64_t *b = reinterpret_cast<uint64_t *>(blob.data() + nd);
+    for (size_t i = 0; i < v.size(); i++) b[i] = v[i].tile_begin;
+    uint32_t *h = reinterpret_cast<uint32_t *>(blob.data() + nd + nb);
+    size_t seg = 0;
+    for (size_t g = 0; g < groups; g++) {
+        const uint64_t first = (uint64_t)g << shift;
+        while (seg + 1 < v.size() && v[seg + 1].tile_begin <= first) seg++;
+        h[g] = (uint32_t)seg;
+    }
+    h[groups] = v.empty() ? 0u : (uint32_t)(v.size() - 1);
+    int32_t rc = table_upload(t, blob.data(), blob.size(), s);
+    if (rc != PSX_OK) return rc;
+    const unsigned char *base = static_cast<const unsigned char *>(t.dev);
+    *items = reinterpret_cast<const CopySeg *>(base);
+    *begins = reinterpret_cast<const uint64_t *>(base + nd);
+    *hints = reinterpret_cast<const uint32_t *>(base + nd + nb);
+    *shift_out = shift;
+    return PSX_OK;
+}
+
 struct TimedSpan {
     hipEvent_t a = nullptr, b = nullptr;
     bool valid = false;
@@ -267,8 +298,8 @@ extern "C" int32_t psx_ctx_create(const psx_ctx_config *cfg, psx_ctx **out) {
     if ((rc = table_reserve(c->move_tbl, cfg->max_chunks * (sizeof(MoveRun) + 8))) != PSX_OK) return bail(rc);
     if ((rc = table_reserve(c->check_tbl, cfg->max_chunks * (sizeof(AdamRun) + 8))) != PSX_OK) return bail(rc);
     const size_t segs = (size_t)cfg->max_tensors + (size_t)cfg->max_chunks + 1;
-    if ((rc = table_reserve(c->pack_tbl, segs * (sizeof(CopySeg) + 8))) != PSX_OK) return bail(rc);
-    if ((rc = table_reserve(c->unpack_tbl, segs * (sizeof(CopySeg) + 8))) != PSX_OK) return bail(rc);
+    if ((rc = table_reserve(c->pack_tbl, segs * (sizeof(CopySeg) + 8) + (kMaxHints + 1) * 4)) != PSX_OK) return bail(rc);
+    if ((rc = table_reserve(c->unpack_tbl, segs * (sizeof(CopySeg) + 8) + (kMaxHints + 1) * 4)) != PSX_OK) return bail(rc);
     *out = c;
     return PSX_OK;
 }
@@ -525,7 +556,7 @@ int32_t build_segments(psx_ctx *c, const char *who, uint32_t dtype, const void *
             g.dst = const_cast<unsigned char *>(to_chunk ? k : t);
             g.n = take; g.tile_begin = tiles; g.chunk = (uint32_t)ck; g.pad = 0;
             c->segs.push_back(g);
-            tiles += (take + tile_elems - 1) / tile_elems;
+            tiles += copy_tiles_of(g.dst, take, es, tile_elems);
             done += take;
         }
         elems += s;
@@ -542,12 +573,14 @@ int32_t run_copy(psx_ctx *c, Table &tbl, uint32_t dtype, uint64_t tiles, bool ch
     if (c->segs.size() > 0xFFFFFFFFull) return fail(PSX_ECAP, "too many copy segments");
     const CopySeg *segs_dev = nullptr;
     const uint64_t *begins_dev = nullptr;
-    rc = upload_described(tbl, c->segs, c->blob, s, &segs_dev, &begins_dev);
+    const uint32_t *hints_dev = nullptr;
+    uint32_t shift = 0;
+    rc = upload_segments(tbl, c->segs, tiles, c->blob, s, &segs_dev, &begins_dev, &hints_dev, &shift);
     if (rc != PSX_OK) return rc;
     if ((rc = span_begin(c, c->t_pack, s)) != PSX_OK) return rc;
     Tuning tn = c->tune;
     tn.copy_unroll = c->copy_unroll_now;
-    PSX_HIP(launch_copy(SegView{segs_dev, begins_dev, (uint32_t)c->segs.size()}, tiles,
+    PSX_HIP(launch_copy(SegView{segs_dev, begins_dev, (uint32_t)c->segs.size(), hints_dev, shift}, tiles,
                         dtype == PSX_F16 ? 2u : 4u, check ? c->flags_dev : nullptr,
                         check ? c->flags_dev + 1 : nullptr, tn, c->n_cu, s));
     return span_end(c, c->t_pack, s);
