@@ -532,14 +532,33 @@ __global__ __launch_bounds__(T) void copy_kernel(const CopySeg *__restrict__ seg
                 // whole tile, source off by `mis` bytes: the two aligned source vectors that cover each
                 // output vector (both hold wanted bytes, so no load leaves the tensor's 16-byte blocks)
                 const PSX_GLOBAL u32x4 *ab = gptr<u32x4>(s - mis);
-                u32x4 lo[U], hi[U];
+                u32x4 lo[U + 1];
 #pragma unroll
-                for (int u = 0; u < U; u++) {
-                    lo[u] = ld<NT>(ab + u * T + tid);
-                    hi[u] = ld<NT>(ab + u * T + tid + 1);
+                for (int u = 0; u < U; u++) lo[u] = ld<NT>(ab + u * T + tid);
+                if constexpr (T == 64) {
+                    // one wavefront: the vector after a lane's own is its neighbour's, handed over lane to lane
+                    // (a wavefront shift); only the vector after the tile's last one is loaded on top, by all
+                    // lanes from one address
+                    lo[U] = ld<NT>(ab + U * T);
+#pragma unroll
+                    for (int u = 0; u < U; u++) {
+                        u32x4 hi;
+#pragma unroll
+                        for (int k = 0; k < 4; k++) {
+                            // lane i takes lane i+1's word of this row; lane 63 has no neighbour and keeps `old`:
+                            // lane 0's word of the next row (for the last row: the extra vector)
+                            const uint32_t next_row_lane0 = __builtin_amdgcn_readfirstlane(lo[u + 1][k]);
+                            hi[k] = (uint32_t)__builtin_amdgcn_update_dpp((int)next_row_lane0, (int)lo[u][k], 0x130, 0xf, 0xf, false);
+                        }
+                        w[u] = shift_pair(lo[u], hi, mis);
+                    }
+                } else {
+#pragma unroll
+                    for (int u = 0; u < U; u++) {
+                        const u32x4 hi = ld<NT>(ab + u * T + tid + 1);
+                        w[u] = shift_pair(lo[u], hi, mis);
+                    }
                 }
-#pragma unroll
-                for (int u = 0; u < U; u++) w[u] = shift_pair(lo[u], hi[u], mis);
             }
 #pragma unroll
             for (int u = 0; u < U; u++) {
