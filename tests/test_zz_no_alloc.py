@@ -116,3 +116,39 @@ def test_noalloc_refuses_what_does_not_fit():
     assert e.value.code == psx.PSX_EINVAL
     torch.cuda.synchronize()
     assert not z.any() and not h.any()
+
+
+def test_noalloc_call_can_be_recorded_into_a_graph():
+    """The callers this entry point is for include code under HIP graph capture: record one call, replay it
+    three times (eager work and synchronisations in between) and compare with three eager calls of the
+    context entry point with the same hyper-parameters on identical inputs."""
+    C, used = 20000, [20000, 4097, 1, 12289]
+    hp = dict(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01, adamw_mode=0, step=5, loss_scale=1024.0)
+    inputs = make_inputs(used, C, 900, alias_every=2, loss_scale=hp["loss_scale"])
+    ref, ref_chunks = upload(inputs, used)
+    got, got_chunks = upload(inputs, used)
+    hyper = psx.make_hyper(**hp)
+    ctx = psx.psx_ctx_create(max_chunks=8, max_tensors=4)
+    try:
+        flag_dev = torch.full((1,), 77, dtype=torch.int32, device=DEV)
+        psx.psx_chunk_adam_step_noalloc(got_chunks, hyper, psx.PSX_STEP_CHECK_FIRST, flag_dev)      # first call on the device, eager
+        psx.psx_chunk_adam_step(ctx, ref_chunks, hyper, psx.PSX_STEP_CHECK_FIRST)
+        torch.cuda.synchronize()
+        assert_same(got, ref, "eager call")
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            psx.psx_chunk_adam_step_noalloc(got_chunks, hyper, psx.PSX_STEP_CHECK_FIRST, flag_dev)
+        for rep in range(3):
+            # the reused fp16 chunks hold parameters after a step: give both sides fresh gradients, as a backward pass would
+            for k in range(len(used)):
+                g = torch.from_numpy(W.grads_f16_np(used[k], 950 + 10 * rep + k, hp["loss_scale"]).view(np.int16).copy()).to(DEV)
+                got["g16"][k][:used[k]] = g
+                ref["g16"][k][:used[k]] = g
+            junk = torch.randn(1 << 14, device=DEV).sum()
+            graph.replay()
+            psx.psx_chunk_adam_step(ctx, ref_chunks, hyper, psx.PSX_STEP_CHECK_FIRST)
+            torch.cuda.synchronize()
+            assert_same(got, ref, f"replay {rep}")
+            assert int(flag_dev.item()) == 0 and torch.isfinite(junk)
+    finally:
+        psx.psx_ctx_destroy(ctx)
