@@ -655,6 +655,8 @@ extern "C" int32_t psx_overflow_check(psx_ctx *c, const void *const *g16_chunks,
     int32_t rc = set_device_guard(c);
     if (rc != PSX_OK) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if ((per_chunk != nullptr || flag_out != nullptr) && capturing(s))
+        return fail(PSX_ECAPTURE, "psx_overflow_check: reading the flags back synchronises and cannot be recorded into a graph (pass NULL for both outputs)");
     const AdamRun *runs_dev = nullptr;
     const uint64_t *begins_dev = nullptr;
     rc = upload_described(c->check_tbl, c->runs, c->blob, s, &runs_dev, &begins_dev);
