@@ -29,10 +29,13 @@
  *
  * Pins: see tests/test_oracle_*.py (the placement cost at the end of this file:
  * tests/test_oracle_planner.py with hand-worked cases under tests/golden/).
- * The loss-scale growth interval and the
- * choice between L2 and decoupled weight decay are conventions, not paper
- * facts: "parity unpinned" for those two (the arithmetic of both decay modes
- * is pinned against a library Adam/AdamW).
+ * The paper fixes neither a loss-scale schedule nor a decay mode.  The
+ * arithmetic of both decay modes is pinned against a library Adam / AdamW, and
+ * the schedule (halve on overflow, double after growth_interval good steps,
+ * a skipped step does not advance t) against a library mixed-precision loop.
+ * What stays a convention of this build, "parity unpinned" by the paper: the
+ * floor of the scale at 1, the default growth interval, and which decay mode
+ * is the default.
  */
 #include <math.h>
 #include <stddef.h>

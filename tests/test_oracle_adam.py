@@ -1,8 +1,11 @@
 """Pins for the oracle's Adam arithmetic: closed forms of Kingma & Ba's
 Algorithm 1, an fp64 evaluation in the textbook (m-hat / v-hat) form, library
 Adam / AdamW, exact power-of-two unscaling, overflow-skip bit identity and the
-fp16 re-cast.  The loss-scale schedule and the default decay mode are
-conventions ("parity unpinned" by the paper); their behaviour is still tested."""
+fp16 re-cast.  The paper fixes neither the loss-scale schedule nor the decay
+mode; the schedule used here (halve on overflow, double after a run of good
+steps, skipped steps do not advance t) is held against PyTorch's own
+mixed-precision loop, its floor at 1 and the default decay mode are conventions
+whose behaviour is tested."""
 import numpy as np
 import pytest
 
@@ -233,6 +236,47 @@ def test_step_scalars(orc):
         assert s.inv_scale == 2.0 ** -16
         assert s.omb1 == pytest.approx(1 - b1, rel=1e-7) and s.omb2 == pytest.approx(1 - b2, rel=1e-7)
         assert s.decay == pytest.approx(1 - lr * 0.01, rel=1e-7)
+
+
+# ---------------------------------------------------------------- the whole loop against library mixed-precision training
+
+def test_skip_and_loss_scale_against_library_amp(orc):
+    """Overflow test, skipped update, unscaling, Adam and the loss-scale schedule together, against PyTorch's own
+    mixed-precision loop on the CPU (torch.amp.GradScaler around torch.optim.Adam): after every step the scale,
+    the run of good steps and the optimizer's step count must be the library's, and the parameters its
+    parameters.  (The library has no floor at 1; the scale stays far above it here.)"""
+    import torch
+    n, gi = 64, 3
+    coeff = (np.arange(n) % 13 - 6).astype(np.float32) / np.float32(1024.0)       # exact in fp16 at every scale used
+    p0 = W.params_np(n, 71)
+    tp = torch.nn.Parameter(torch.from_numpy(p0.copy()))
+    opt = torch.optim.Adam([tp], lr=1e-3, betas=(0.9, 0.999), eps=1e-8, weight_decay=0.0)
+    amp = torch.amp.GradScaler("cpu", init_scale=1024.0, growth_factor=2.0, backoff_factor=0.5, growth_interval=gi)
+    s = orc.scaler(1024.0, gi)
+    g16 = [np.zeros(n, np.uint16)]
+    p16, p, m, v = [np.zeros(n, np.uint16)], [p0.copy()], [np.zeros(n, F32)], [np.zeros(n, F32)]
+    used = np.array([n], np.uint64)
+    bad_steps = {4, 5, 11, 20, 21, 22}
+    seen = set()
+    for it in range(30):
+        c = coeff * np.float32(1 + it % 3)
+        ct = torch.from_numpy(c.copy())
+        if it in bad_steps:
+            ct[it % n] = float("inf") if it % 2 else float("nan")
+        opt.zero_grad()
+        amp.scale((tp * ct).sum()).backward()
+        amp.step(opt)
+        amp.update()
+        with np.errstate(over="ignore", invalid="ignore"):
+            g16[0][:] = (ct.numpy() * np.float32(s.scale)).astype(np.float16).view(np.uint16)
+        flag = orc.chunk_adam_step(g16, p16, p, m, v, used, orc.hyper(weight_decay=0.0, step=s.step, loss_scale=s.scale))
+        orc.scaler_update(s, flag)
+        assert flag == int(it in bad_steps)
+        assert s.scale == amp.get_scale() and s.good_steps == int(amp._growth_tracker.item())
+        assert s.step - 1 == (int(opt.state[tp]["step"]) if tp in opt.state else 0)
+        assert np.allclose(p[0], tp.detach().numpy(), rtol=0, atol=(it + 1) * 5e-8)
+        seen.add(s.scale)
+    assert len(seen) >= 3 and s.step == 31 - len(bad_steps)       # the scale both grew and shrank on the way
 
 
 # ---------------------------------------------------------------- loss-scale convention (unpinned by the paper)
