@@ -430,11 +430,15 @@ def timed_steps(st, steps, warmup, fused_check, plans=None):
     link = {"h2d": 0, "d2h": 0, "min_h2d": 0, "min_d2h": 0, "moved_chunks": 0, "resident_chunks": []}
     skipped = 0
     tm = None
+    each_step, each_adam = [], []
     t0 = time.perf_counter()
     for i in range(steps):
         before = list(st.loc)
+        ts = time.perf_counter()
         skipped += run_step(st, fused_check, plan_at(1 + warmup + i))
-        tm = psx.psx_ctx_get_timing(st.ctx)      # events of this step; the stream is already drained
+        each_step.append((time.perf_counter() - ts) * 1e3)   # the step ends with the flag read back: the stream is drained
+        tm = psx.psx_ctx_get_timing(st.ctx)      # events of this step
+        each_adam.append(tm.adam_ms)
         phase["pack_ms"] += tm.pack_ms; phase["check_ms"] += tm.check_ms
         phase["adam_ms"] += tm.adam_ms; phase["spill_ms"] += tm.spill_ms
         # every chunk that starts the step on the host must come in once, every chunk that ends it there
@@ -449,7 +453,18 @@ def timed_steps(st, steps, warmup, fused_check, plans=None):
     sums = dict(phase)
     for k in phase:
         phase[k] /= max(steps, 1)
-    return {"ms": dt * 1e3 / max(steps, 1), "phase": phase, "phase_sum_ms": sums, "link": link, "tm": tm, "skipped": skipped}
+    return {"ms": dt * 1e3 / max(steps, 1), "phase": phase, "phase_sum_ms": sums, "link": link, "tm": tm, "skipped": skipped,
+            "step_ms": spread(each_step), "adam_launch_ms": spread(each_adam)}
+
+
+def spread(xs):
+    """Median, minimum and maximum of per-step times."""
+    if not xs:
+        return None
+    xs = sorted(xs)
+    mid = len(xs) // 2
+    med = xs[mid] if len(xs) % 2 else 0.5 * (xs[mid - 1] + xs[mid])
+    return {"median": med, "min": xs[0], "max": xs[-1]}
 
 
 def plain_copy_rate(ctx, dev):
@@ -477,7 +492,8 @@ def adam_roofline(r, copy_gbs=None):
     ms = r["phase"]["adam_ms"]
     achieved = adam_bytes / (ms * 1e-3) / 1e9 if ms > 0 else 0.0
     out = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-           "kernel": "psx::adam_kernel (resident chunks, one launch)", "bytes_per_launch": adam_bytes, "avg_launch_ms": ms}
+           "kernel": "psx::adam_kernel (resident chunks, one launch)", "bytes_per_launch": adam_bytes, "avg_launch_ms": ms,
+           "launch_ms": r.get("adam_launch_ms")}
     if copy_gbs:
         out.update(same_run_plain_copy_GBs=copy_gbs, frac_of_plain_copy=achieved / copy_gbs)
     return out
@@ -746,7 +762,7 @@ def main():
         "metric": "chunked Adam Gelem/s (whole hot path per step: layout + grad pack + overflow check + fused Adam + fp16 unpack + loss-scale update)",
         "value": n_elems / (ms * 1e-3) / 1e9,
         "unit": "Gelem/s",
-        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms,
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms, "step_ms": r["step_ms"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "scaled_from": scaled_from, "n_elems": n_elems, "n_tensors": len(w.numel),
