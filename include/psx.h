@@ -179,7 +179,9 @@ int32_t psx_overflow_read(psx_ctx *ctx, uint32_t *per_chunk, size_t n_chunks, ui
  * multiply-add).  Step-wide scalars are derived in double from the doubles
  * below and rounded to fp32 once:
  *   step_size = lr/(1-beta1^t), c2 = 1/sqrt(1-beta2^t), inv_scale = 1/loss_scale,
- *   beta1, beta2, 1-beta1, 1-beta2, eps, weight_decay, decay = 1-lr*weight_decay.
+ *   beta1, beta2, 1-beta1, 1-beta2, eps, weight_decay, decay = 1-lr*weight_decay,
+ * where beta^t is the product of t factors beta, each multiplication rounded to
+ * double (not libm's pow, which differs from it in the last bits).
  * Per element k < used:
  *   g = f32(g16[k]) * inv_scale
  *   weight_decay != 0, adamw_mode == 0:  g = g + weight_decay*p      (L2)

@@ -133,6 +133,27 @@ int32_t upload_segments(Table &t, const std::vector<CopySeg> &v, uint64_t n_tile
     return PSX_OK;
 }
 
+// beta^t as what it is defined to be here: the product of t factors, each multiplication rounded to double.
+// (libm's pow approximates the real power more closely and is, for that very reason, not always the same
+// double; once in a long while the difference moves a scalar rounded to fp32: with beta2 = 0.999999, c2 of
+// step 12314 is one fp32 ulp apart between the two.)
+// A training loop asks for t, t, t+1, t+2, ...: the product of this thread's last call is continued when
+// beta is the same and t has not gone back, so the usual call costs one multiplication.
+struct PowerByProduct {
+    double beta = -1.0, prod = 1.0;
+    uint64_t t = 0;
+    double operator()(double b, uint64_t steps) {
+        if (b != beta || steps < t) { beta = b; prod = 1.0; t = 0; }
+        while (t < steps) {
+            if (prod == 0.0) { t = steps; break; }      // underflowed: every further factor leaves it at zero
+            prod = prod * b;
+            t++;
+        }
+        return prod;
+    }
+};
+thread_local PowerByProduct g_pow1, g_pow2;
+
 struct TimedSpan {
     hipEvent_t a = nullptr, b = nullptr;
     bool valid = false;
@@ -690,8 +711,8 @@ extern "C" int32_t psx_step_state_init(psx_ctx *c, const psx_adam_hyper *hyper, 
     init.growth_interval = scaler->growth_interval;
     init.good_steps = scaler->good_steps;
     init.step = scaler->step;
-    init.b1t = 1.0; init.b2t = 1.0;
-    for (uint64_t i = 0; i < scaler->step; i++) { init.b1t = init.b1t * h.beta1; init.b2t = init.b2t * h.beta2; }
+    init.b1t = PowerByProduct{}(h.beta1, scaler->step);
+    init.b2t = PowerByProduct{}(h.beta2, scaler->step);
     init.lr = h.lr; init.beta1 = h.beta1; init.beta2 = h.beta2;
     PSX_HIP(launch_step_state_init(c->state_dev, init, static_cast<hipStream_t>(stream)));
     c->state_hyper = h;
@@ -740,9 +761,8 @@ int32_t prepare_adam_scalars(const psx_adam_hyper *h, const char *who, AdamScala
     if (h->step == 0) return fail(PSX_EINVAL, "%s: step is 1-based", who);
     if (!(h->beta1 >= 0.0 && h->beta1 < 1.0) || !(h->beta2 >= 0.0 && h->beta2 < 1.0))
         return fail(PSX_EINVAL, "%s: betas must lie in [0, 1)", who);
-    const double t = (double)h->step;
-    const double b1t = std::pow(h->beta1, t);
-    const double b2t = std::pow(h->beta2, t);
+    const double b1t = g_pow1(h->beta1, h->step);
+    const double b2t = g_pow2(h->beta2, h->step);
     s->step_size = (float)(h->lr / (1.0 - b1t));
     s->c2 = (float)(1.0 / std::sqrt(1.0 - b2t));
     s->inv_scale = (float)(1.0 / h->loss_scale);

@@ -147,9 +147,17 @@ def test_noalloc_step_validates_before_it_touches_the_gpu():
 
 
 def test_step_scalars_agree_with_the_oracle_over_many_steps(orc):
-    """The library derives beta^t with libm pow, the oracle as the t-fold product: two derivations that
-    share nothing.  After rounding to fp32 all ten scalars must be the same numbers at every step the
-    tests and benchmarks can reach (every t up to 20000, then every 97th up to 10^5), for several betas."""
+    """Library and oracle both define beta^t as the product of t factors in double, each in code of its
+    own (the library continues the product of its last call, the oracle starts from 1 every time).  All
+    ten scalars must be the same fp32 numbers at every step: every t up to 20000, then every 97th up to
+    10^5, for several betas; steps asked for out of order; a power that has underflowed to zero; and the
+    one step found where libm's pow would have given another c2 (beta2 = 0.999999, t = 12314)."""
+    def same(hp, t):
+        mine = psx.psx_adam_step_scalars(psx.make_hyper(step=t, **hp))
+        ref = orc.adam_prepare(orc.hyper(step=t, **hp))
+        for name in psx.SCALAR_NAMES:
+            assert mine[name] == getattr(ref, name), (hp, t, name)
+        return mine
     cases = [dict(lr=1e-3, beta1=0.9, beta2=0.999, weight_decay=0.01, loss_scale=65536.0),
              dict(lr=3e-4, beta1=0.95, beta2=0.98, weight_decay=0.1, adamw_mode=1, loss_scale=1024.0),
              dict(lr=1e-2, beta1=0.8, beta2=0.9999, eps=1e-6, loss_scale=1.0),
@@ -157,10 +165,16 @@ def test_step_scalars_agree_with_the_oracle_over_many_steps(orc):
     for i, hp in enumerate(cases):
         steps = list(range(1, 20001 if i == 0 else 2001)) + list(range(20001, 100001, 97 if i == 0 else 4999))
         for t in steps:
-            mine = psx.psx_adam_step_scalars(psx.make_hyper(step=t, **hp))
-            ref = orc.adam_prepare(orc.hyper(step=t, **hp))
-            for name in psx.SCALAR_NAMES:
-                assert mine[name] == getattr(ref, name), (hp, t, name)
+            same(hp, t)
+    near_one = dict(lr=1e-3, beta1=0.9, beta2=0.999999, loss_scale=1.0)
+    import math
+    for t in (12313, 12314, 12315, 7, 12314, 1, 250000, 12314):          # forwards, back, and again
+        got = same(near_one, t)
+    by_pow = np.float32(1.0 / math.sqrt(1.0 - math.pow(0.999999, 12314)))
+    assert got["c2"] != by_pow and abs(float(got["c2"]) - float(by_pow)) <= float(np.spacing(by_pow))
+    for t in (3_000_000, 2_999_999, 3_000_001):                           # 0.999^t is zero in double by then
+        got = same(cases[0], t)
+        assert got["c2"] == 1.0 and got["step_size"] == np.float32(1e-3)
     with pytest.raises(psx.PsxError):
         psx.psx_adam_step_scalars(psx.make_hyper(step=0))
     with pytest.raises(psx.PsxError):
