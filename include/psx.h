@@ -361,7 +361,7 @@ int32_t psx_ctx_set_tuning(psx_ctx *ctx, uint32_t key, int64_t value);
 
 /* Kernel timing with HIP events on the caller's stream (off by default). */
 typedef struct psx_timing {
-    float pack_ms;     /* last psx_pack / psx_unpack copy kernel                           */
+    float pack_ms;     /* last psx_pack copy kernel                                        */
     float check_ms;    /* last overflow check kernel                                       */
     float adam_ms;     /* last resident (HBM->HBM) Adam kernel launch                      */
     float spill_ms;    /* last streamed part: first H2D issued to last D2H done            */
@@ -371,6 +371,8 @@ typedef struct psx_timing {
     float cpu_ms;          /* last PSX_EXEC_CPU part: host wall time, first tile to last   */
     uint32_t cpu_threads;  /* worker threads it used                                       */
     uint64_t cpu_elems;    /* elements updated by the host cores                           */
+    float unpack_ms;       /* last psx_unpack copy kernel                                  */
+    uint32_t reserved;
 } psx_timing;
 int32_t psx_ctx_set_profiling(psx_ctx *ctx, int32_t on);
 /* Synchronises the recorded events, then fills *out (fields of phases not run are 0). */

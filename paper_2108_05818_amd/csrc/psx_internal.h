@@ -110,11 +110,17 @@ constexpr uint64_t kCheckTileElems = (uint64_t)kThreads * 8u * 4u;   // 8192 fp1
 // tensors, so 1 KiB tiles win there as well (5000-tensor workload: 0.93 ms against 0.99 with 4 KiB tiles).
 inline int copy_unroll_for(const Tuning &t, size_t) { return t.copy_unroll != 0 ? t.copy_unroll : 1; }
 // Tiles of one copy segment (n elements of es bytes written to dst): a first tile of the elements in front
-// of the destination's first 16-byte boundary, if any, then whole tiles from that boundary on.  The copy
-// kernel maps tile indices to elements by the same rule.
+// of the destination's first kCopyCutBytes boundary, if any, then whole tiles from that boundary on, so that
+// every whole tile writes whole 128-byte lines (a tile that starts in the middle of a line shares its first
+// and last line with the tiles next to it, which run on other XCDs: two partial writes per line instead of
+// one full one).  The copy kernel maps tile indices to elements by the same rule.
+constexpr uint32_t kCopyCutBytes = 128;
+inline uint64_t copy_head_elems(const void *dst, uint64_t n, uint32_t es) {
+    const uint64_t a = ((kCopyCutBytes - (uint32_t)(reinterpret_cast<uintptr_t>(dst) & (kCopyCutBytes - 1u))) & (kCopyCutBytes - 1u)) / es;
+    return a > n ? n : a;
+}
 inline uint64_t copy_tiles_of(const void *dst, uint64_t n, uint32_t es, uint64_t tile_elems) {
-    uint64_t a = ((16u - (uint32_t)(reinterpret_cast<uintptr_t>(dst) & 15u)) & 15u) / es;
-    if (a > n) a = n;
+    const uint64_t a = copy_head_elems(dst, n, es);
     return (a != 0 ? 1u : 0u) + (n - a + tile_elems - 1) / tile_elems;
 }
 inline uint64_t copy_tile_bytes(const Tuning &t, int unroll) { return (uint64_t)(t.copy_threads == 64 ? 64 : 256) * 16u * (uint64_t)(unroll == 1 ? 1 : 4); }

@@ -482,12 +482,13 @@ __device__ __forceinline__ u32x4 shift_pair(const u32x4 &lo, const u32x4 &hi, ui
     return w;
 }
 
-// Tiles of a segment are cut so that the destination of every tile but the first starts on a 16-byte
-// boundary: a segment whose destination is misaligned by `a` elements gets a first tile of just those `a`
-// elements, and tiles of TILE_ELEMS elements after it.  (The host counts tiles by the same rule, see
-// copy_tiles_of.)  Whole tiles then never need element-wise heads or tails: they are copied with U
-// 16-byte loads and stores per lane, straight when the source shares the alignment, else from pairs of
-// aligned source vectors shifted into place; only a segment's first and last tile take the general path.
+// Tiles of a segment are cut so that the destination of every tile but the first starts on a
+// kCopyCutBytes (128-byte) boundary: a segment whose destination is `a` elements short of one gets a
+// first tile of just those `a` elements, and tiles of TILE_ELEMS elements after it.  (The host counts
+// tiles by the same rule, see copy_tiles_of.)  Whole tiles then write whole lines and never need
+// element-wise heads or tails: they are copied with U 16-byte loads and stores per lane, straight when
+// the source shares the 16-byte alignment, else from pairs of aligned source vectors shifted into
+// place; only a segment's first and last tile take the general path.
 template <int ES, bool CHECK, bool NT, int U, int T>
 __global__ __launch_bounds__(T) void copy_kernel(const CopySeg *__restrict__ segs,
                                                         const uint64_t *__restrict__ begins,
@@ -502,7 +503,7 @@ __global__ __launch_bounds__(T) void copy_kernel(const CopySeg *__restrict__ seg
         const uint32_t r = find_owner_hinted(begins, hints, shift, tile);
         const uint64_t n = segs[r].n;
         const uint64_t t_in = tile - segs[r].tile_begin;
-        uint64_t a = ((16u - (uint32_t)(reinterpret_cast<uintptr_t>(segs[r].dst) & 15u)) & 15u) / ES;   // elements up to the boundary
+        uint64_t a = ((kCopyCutBytes - (uint32_t)(reinterpret_cast<uintptr_t>(segs[r].dst) & (kCopyCutBytes - 1u))) & (kCopyCutBytes - 1u)) / ES;   // elements up to the boundary
         if (a > n) a = n;
         uint64_t base;
         uint32_t cnt;

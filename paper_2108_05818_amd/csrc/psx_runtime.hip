@@ -196,7 +196,7 @@ struct psx_ctx {
     std::vector<hipEvent_t> ev_h2d, ev_k, ev_free;
     hipEvent_t ev_entry = nullptr, ev_h2d_end = nullptr, ev_d2h_end = nullptr;
     bool prof = false;
-    TimedSpan t_pack, t_check, t_adam, t_spill;
+    TimedSpan t_pack, t_unpack, t_check, t_adam, t_spill;
     uint64_t adam_elems = 0, spill_elems = 0, h2d_bytes = 0, d2h_bytes = 0;
     std::vector<AdamRun> runs;         // scratch for table building
     std::vector<MoveRun> moves;
@@ -304,7 +304,7 @@ extern "C" int32_t psx_ctx_create(const psx_ctx_config *cfg, psx_ctx **out) {
         PSX_TRY(hipEventCreateWithFlags(&c->ev_k[i], hipEventDisableTiming));
         PSX_TRY(hipEventCreateWithFlags(&c->ev_free[i], hipEventDisableTiming));
     }
-    for (TimedSpan *t : {&c->t_pack, &c->t_check, &c->t_adam, &c->t_spill}) {
+    for (TimedSpan *t : {&c->t_pack, &c->t_unpack, &c->t_check, &c->t_adam, &c->t_spill}) {
         PSX_TRY(hipEventCreate(&t->a));
         PSX_TRY(hipEventCreate(&t->b));
     }
@@ -358,7 +358,7 @@ extern "C" int32_t psx_ctx_destroy(psx_ctx *c) {
     for (auto *vec : {&c->ev_h2d, &c->ev_k, &c->ev_free})
         for (hipEvent_t e : *vec)
             if (e) note(hipEventDestroy(e), "hipEventDestroy");
-    for (TimedSpan *t : {&c->t_pack, &c->t_check, &c->t_adam, &c->t_spill}) {
+    for (TimedSpan *t : {&c->t_pack, &c->t_unpack, &c->t_check, &c->t_adam, &c->t_spill}) {
         if (t->a) note(hipEventDestroy(t->a), "hipEventDestroy");
         if (t->b) note(hipEventDestroy(t->b), "hipEventDestroy");
     }
@@ -436,16 +436,16 @@ extern "C" int32_t psx_ctx_set_tuning(psx_ctx *c, uint32_t key, int64_t value) {
 extern "C" int32_t psx_ctx_set_profiling(psx_ctx *c, int32_t on) {
     if (c == nullptr) return fail(PSX_EINVAL, "psx_ctx_set_profiling: ctx is NULL");
     c->prof = on != 0;
-    for (TimedSpan *t : {&c->t_pack, &c->t_check, &c->t_adam, &c->t_spill}) t->valid = false;
+    for (TimedSpan *t : {&c->t_pack, &c->t_unpack, &c->t_check, &c->t_adam, &c->t_spill}) t->valid = false;
     return PSX_OK;
 }
 
 extern "C" int32_t psx_ctx_get_timing(psx_ctx *c, psx_timing *out) {
     if (c == nullptr || out == nullptr) return fail(PSX_EINVAL, "psx_ctx_get_timing: NULL argument");
     memset(out, 0, sizeof(*out));
-    float *dst[4] = {&out->pack_ms, &out->check_ms, &out->adam_ms, &out->spill_ms};
-    TimedSpan *src[4] = {&c->t_pack, &c->t_check, &c->t_adam, &c->t_spill};
-    for (int i = 0; i < 4; i++) {
+    float *dst[5] = {&out->pack_ms, &out->unpack_ms, &out->check_ms, &out->adam_ms, &out->spill_ms};
+    TimedSpan *src[5] = {&c->t_pack, &c->t_unpack, &c->t_check, &c->t_adam, &c->t_spill};
+    for (int i = 0; i < 5; i++) {
         if (!src[i]->valid) continue;
         PSX_HIP(hipEventSynchronize(src[i]->b));
         PSX_HIP(hipEventElapsedTime(dst[i], src[i]->a, src[i]->b));
@@ -587,7 +587,7 @@ int32_t build_segments(psx_ctx *c, const char *who, uint32_t dtype, const void *
     return PSX_OK;
 }
 
-int32_t run_copy(psx_ctx *c, Table &tbl, uint32_t dtype, uint64_t tiles, bool check, hipStream_t s) {
+int32_t run_copy(psx_ctx *c, Table &tbl, TimedSpan &span, uint32_t dtype, uint64_t tiles, bool check, hipStream_t s) {
     int32_t rc = set_device_guard(c);
     if (rc != PSX_OK) return rc;
     if (tiles == 0) return PSX_OK;
@@ -598,13 +598,13 @@ int32_t run_copy(psx_ctx *c, Table &tbl, uint32_t dtype, uint64_t tiles, bool ch
     uint32_t shift = 0;
     rc = upload_segments(tbl, c->segs, tiles, c->blob, s, &segs_dev, &begins_dev, &hints_dev, &shift);
     if (rc != PSX_OK) return rc;
-    if ((rc = span_begin(c, c->t_pack, s)) != PSX_OK) return rc;
+    if ((rc = span_begin(c, span, s)) != PSX_OK) return rc;
     Tuning tn = c->tune;
     tn.copy_unroll = c->copy_unroll_now;
     PSX_HIP(launch_copy(SegView{segs_dev, begins_dev, (uint32_t)c->segs.size(), hints_dev, shift}, tiles,
                         dtype == PSX_F16 ? 2u : 4u, check ? c->flags_dev : nullptr,
                         check ? c->flags_dev + 1 : nullptr, tn, c->n_cu, s));
-    return span_end(c, c->t_pack, s);
+    return span_end(c, span, s);
 }
 
 }  // namespace
@@ -618,7 +618,7 @@ extern "C" int32_t psx_pack(psx_ctx *c, uint32_t dtype, const void *const *tenso
     uint64_t tiles = 0, elems = 0;
     int32_t rc = build_segments(c, "psx_pack", dtype, tensors, slots, n, chunks, n_chunks, chunk_elems, true, &tiles, &elems);
     if (rc != PSX_OK) return rc;
-    return run_copy(c, c->pack_tbl, dtype, tiles, (flags & PSX_PACK_CHECK_OVERFLOW) != 0, static_cast<hipStream_t>(stream));
+    return run_copy(c, c->pack_tbl, c->t_pack, dtype, tiles, (flags & PSX_PACK_CHECK_OVERFLOW) != 0, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int32_t psx_unpack(psx_ctx *c, uint32_t dtype, void *const *tensors, const psx_slot *slots,
@@ -628,7 +628,7 @@ extern "C" int32_t psx_unpack(psx_ctx *c, uint32_t dtype, void *const *tensors, 
     uint64_t tiles = 0, elems = 0;
     int32_t rc = build_segments(c, "psx_unpack", dtype, tensors, slots, n, chunks, n_chunks, chunk_elems, false, &tiles, &elems);
     if (rc != PSX_OK) return rc;
-    return run_copy(c, c->unpack_tbl, dtype, tiles, false, static_cast<hipStream_t>(stream));
+    return run_copy(c, c->unpack_tbl, c->t_unpack, dtype, tiles, false, static_cast<hipStream_t>(stream));
 }
 
 // ====================================================================== overflow flag

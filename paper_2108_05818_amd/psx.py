@@ -72,7 +72,7 @@ class psx_timing(C.Structure):
     _fields_ = [("pack_ms", C.c_float), ("check_ms", C.c_float), ("adam_ms", C.c_float), ("spill_ms", C.c_float),
                 ("adam_elems", C.c_uint64), ("spill_elems", C.c_uint64), ("h2d_bytes", C.c_uint64),
                 ("d2h_bytes", C.c_uint64), ("cpu_ms", C.c_float), ("cpu_threads", C.c_uint32),
-                ("cpu_elems", C.c_uint64)]
+                ("cpu_elems", C.c_uint64), ("unpack_ms", C.c_float), ("reserved", C.c_uint32)]
 
 
 class psx_link_rates(C.Structure):
