@@ -631,6 +631,60 @@ def test_step_on_a_side_stream_orders_itself_with_that_stream(orc):
                 b.free()
 
 
+def test_two_contexts_on_two_streams_at_once(orc):
+    """Two contexts, each with its own stream and chunk lists (one of them partly host-resident), stepping
+    at the same time for several steps without a device-wide synchronisation in between: each sequence
+    of steps must come out as if it had run alone."""
+    ctxs = [psx.psx_ctx_create(max_chunks=8, max_tensors=4, staging_tile_elems=4096, staging_slots=2) for _ in range(2)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    host = []
+    try:
+        Cn = 150000
+        used = [[150000, 70001, 12345], [99999, 150000, 1, 4096]]
+        locs = [[(G, G)] * 3, [(G, G), (H, H), (G, G), (H, H)]]
+        cls, specs = [], []
+        for j in range(2):
+            cl = ChunkLists(used[j], Cn)
+            fill_state(cl, 4400 + j, 512.0, zero_mv=False)
+            hs_all = []
+            for k in range(cl.n):
+                hs = [psx.PinnedF32(Cn, fill=0.0) for _ in range(3)]
+                if locs[j][k][0] == H:
+                    for hbuf, name in zip(hs, ("p32", "m", "v")):
+                        hbuf.np[...] = cl.np[name][k]
+                        getattr(cl, name)[k].view(torch.int32).fill_(0x0BADBEEF)
+                hs_all.append(hs)
+            host.append(hs_all)
+            cls.append(cl)
+            specs.append(cl.specs(loc=locs[j], host=hs_all))
+        torch.cuda.synchronize()
+        hps = [dict(lr=1e-3, weight_decay=0.01, loss_scale=512.0), dict(lr=3e-4, beta1=0.8, beta2=0.99, weight_decay=0.1, adamw_mode=1, loss_scale=512.0)]
+        steps = 4
+        for t in range(1, steps + 1):
+            for j in range(2):
+                with torch.cuda.stream(streams[j]):
+                    psx.psx_chunk_adam_step(ctxs[j], psx.make_chunks(specs[j]), psx.make_hyper(step=t, **hps[j]), psx.PSX_STEP_CHECK_FIRST)
+        for st in streams:
+            st.synchronize()
+        for j in range(2):
+            for t in range(1, steps + 1):
+                assert cls[j].oracle_step(orc, orc.hyper(step=t, **hps[j])) == 0
+            for k in range(cls[j].n):
+                u = used[j][k]
+                assert np.array_equal(bits16(cls[j].p16[k])[:u], cls[j].np["p16"][k][:u]), (j, k)
+                for i, name in enumerate(("p32", "m", "v")):
+                    got = host[j][k][i].np if locs[j][k][1] == H else f32(getattr(cls[j], name)[k])
+                    assert got[:u].tobytes() == cls[j].np[name][k][:u].tobytes(), (j, k, name)
+    finally:
+        torch.cuda.synchronize()
+        for c in ctxs:
+            psx.psx_ctx_destroy(c)
+        for hs_all in host:
+            for hs in hs_all:
+                for b in hs:
+                    b.free()
+
+
 @pytest.mark.parametrize("exec_cpu", [0, 1])
 def test_fp32_denormals_are_kept(orc, exec_cpu):
     """A huge loss scale with tiny gradients drives g, m, v and the products on the way through the fp32
