@@ -7,7 +7,8 @@
  * compares its output with the oracle's bit for bit.
  *
  *   c_abi_driver IN OUT
- * IN : u64 magic, n, C, steps, adamw, growth_interval; f64 lr, beta1, beta2, eps, wd, scale0;
+ * IN : u64 magic, n, C, steps, adamw, growth_interval, host_from; f64 lr, beta1, beta2, eps, wd, scale0;
+ *      (chunks with index >= host_from keep their fp32 states in pinned host memory and are updated over the link)
  *      u64 numel[n]; f32 p32[N]; steps x u16 g16[N]          (N = sum of numel, tensors back to back)
  * OUT: u64 n_chunks; u64 used[n_chunks]; steps x {u32 flag, f32 scale after the step};
  *      per chunk: f32 p32[used], m[used], v[used], u16 p16[used]; u16 unpacked p16 tensors [N]
@@ -49,13 +50,13 @@ int main(int argc, char **argv) {
     }
     FILE *in = fopen(argv[1], "rb");
     if (!in) { perror(argv[1]); return 1; }
-    uint64_t head[6];
+    uint64_t head[7];
     double hp[6];
     if (!read_exact(in, head, sizeof head) || !read_exact(in, hp, sizeof hp) || head[0] != MAGIC) {
         fprintf(stderr, "bad input header\n");
         return 1;
     }
-    const uint64_t n = head[1], C = head[2], steps = head[3], adamw = head[4], growth = head[5];
+    const uint64_t n = head[1], C = head[2], steps = head[3], adamw = head[4], growth = head[5], host_from = head[6];
     uint64_t *numel = (uint64_t *)malloc((n ? n : 1) * sizeof(uint64_t));
     if (!numel || !read_exact(in, numel, n * sizeof(uint64_t))) { fprintf(stderr, "bad input: sizes\n"); return 1; }
     uint64_t N = 0;
@@ -117,6 +118,23 @@ int main(int argc, char **argv) {
     psx_ctx *ctx = NULL;
     PSX_CALL(psx_ctx_create(&cfg, &ctx));
     PSX_CALL(psx_pack(ctx, PSX_F32, t_p32, slots, (size_t)n, c_p32, n_chunks, C, 0, NULL));
+    HIP_OK(hipDeviceSynchronize());
+    /* host-resident chunks: pinned homes for the used prefix; the packed parameters move there, and the
+     * device copies are overwritten so that a kernel reading the wrong home would show */
+    for (size_t k = (size_t)host_from; k < n_chunks; k++) {
+        if (used[k] == 0) continue;
+        void *hb[3] = {NULL, NULL, NULL};
+        for (int j = 0; j < 3; j++) {
+            PSX_CALL(psx_pinned_alloc(used[k] * sizeof(float), &hb[j]));
+            memset(hb[j], 0, used[k] * sizeof(float));
+        }
+        HIP_OK(hipMemcpy(hb[0], p32 + k * C, used[k] * sizeof(float), hipMemcpyDeviceToHost));
+        HIP_OK(hipMemset(p32 + k * C, 0x5a, used[k] * sizeof(float)));
+        HIP_OK(hipMemset(m + k * C, 0x5a, used[k] * sizeof(float)));
+        HIP_OK(hipMemset(v + k * C, 0x5a, used[k] * sizeof(float)));
+        chunks[k].p32_host = hb[0]; chunks[k].m_host = hb[1]; chunks[k].v_host = hb[2];
+        chunks[k].loc_in = chunks[k].loc_out = PSX_LOC_HOST;
+    }
 
     FILE *out = fopen(argv[2], "wb");
     if (!out) { perror(argv[2]); return 1; }
@@ -148,8 +166,10 @@ int main(int argc, char **argv) {
     if (!h_f || !h_h) return 1;
     for (size_t k = 0; k < n_chunks; k++) {
         const float *lists[3] = {p32 + k * C, m + k * C, v + k * C};
+        const void *homes[3] = {chunks[k].p32_host, chunks[k].m_host, chunks[k].v_host};
         for (int j = 0; j < 3; j++) {
-            HIP_OK(hipMemcpy(h_f, lists[j], used[k] * sizeof(float), hipMemcpyDeviceToHost));
+            if (chunks[k].loc_out == PSX_LOC_HOST && used[k] != 0) memcpy(h_f, homes[j], used[k] * sizeof(float));
+            else HIP_OK(hipMemcpy(h_f, lists[j], used[k] * sizeof(float), hipMemcpyDeviceToHost));
             if (!write_exact(out, h_f, used[k] * sizeof(float))) return 1;
         }
         HIP_OK(hipMemcpy(h_h, p16 + k * C, used[k] * sizeof(uint16_t), hipMemcpyDeviceToHost));
@@ -160,6 +180,11 @@ int main(int argc, char **argv) {
     if (fclose(out) != 0) return 1;
     fclose(in);
     PSX_CALL(psx_ctx_destroy(ctx));
+    for (size_t k = 0; k < n_chunks; k++) {
+        PSX_CALL(psx_pinned_free(chunks[k].p32_host));
+        PSX_CALL(psx_pinned_free(chunks[k].m_host));
+        PSX_CALL(psx_pinned_free(chunks[k].v_host));
+    }
     HIP_OK(hipFree(d_p32_t)); HIP_OK(hipFree(d_g16_t)); HIP_OK(hipFree(d_p16_t));
     HIP_OK(hipFree(g16)); HIP_OK(hipFree(p16)); HIP_OK(hipFree(p32)); HIP_OK(hipFree(m)); HIP_OK(hipFree(v));
     printf("c_abi_driver: %llu tensors, %llu elements, %zu chunks, %llu steps done\n", (unsigned long long)n,

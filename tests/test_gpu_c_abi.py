@@ -18,7 +18,7 @@ MAGIC = 0x7073785f63616269
 pytestmark = pytest.mark.gpu
 
 
-def run_case(orc, tmp_path, numel, C, steps, hp, scale0, growth, bad_steps):
+def run_case(orc, tmp_path, numel, C, steps, hp, scale0, growth, bad_steps, host_from=1 << 40):
     assert os.path.exists(DRIVER), f"{DRIVER} is missing: build it with `python __graft_entry__.py`"
     n, N = len(numel), int(sum(numel))
     params = [W.params_np(s, 8100 + i) for i, s in enumerate(numel)]
@@ -45,7 +45,7 @@ def run_case(orc, tmp_path, numel, C, steps, hp, scale0, growth, bad_steps):
 
     fin, fout = tmp_path / "in.bin", tmp_path / "out.bin"
     with open(fin, "wb") as f:
-        f.write(struct.pack("<6Q", MAGIC, n, C, steps, int(hp.get("adamw_mode", 0)), growth))
+        f.write(struct.pack("<7Q", MAGIC, n, C, steps, int(hp.get("adamw_mode", 0)), growth, host_from))
         f.write(struct.pack("<6d", hp["lr"], hp["beta1"], hp["beta2"], hp["eps"], hp["weight_decay"], scale0))
         f.write(np.asarray(numel, np.uint64).tobytes())
         for p in params:
@@ -89,6 +89,15 @@ def test_plain_c_program_matches_the_oracle(orc, tmp_path):
     trace = run_case(orc, tmp_path, numel, 4104, 7, hp, 1024.0, 2, bad_steps={2, 5})
     assert [f for f, _ in trace] == [0, 0, 1, 0, 0, 1, 0]
     assert {s for _, s in trace} == {1024.0, 2048.0}
+
+
+def test_plain_c_program_with_host_resident_chunks(orc, tmp_path):
+    """The same list with the fp32 states of chunks 2.. in pinned host memory (psx_pinned_alloc), updated over
+    the link by the kernel under the system HIP runtime; one overflow."""
+    numel = [1, 4000, 7, 9001, 333, 1, 2049, 4104, 15, 640]
+    hp = dict(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01, adamw_mode=0)
+    trace = run_case(orc, tmp_path, numel, 4104, 5, hp, 1024.0, 2, bad_steps={1}, host_from=2)
+    assert [f for f, _ in trace] == [0, 1, 0, 0, 0]
 
 
 def test_plain_c_program_decoupled_decay_one_chunk(orc, tmp_path):
