@@ -829,37 +829,9 @@ int32_t ensure_cpu(psx_ctx *c) {
     return PSX_OK;
 }
 
-}  // namespace
-
-extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size_t n_chunks,
-                                       const psx_adam_hyper *hyper, uint32_t flags, void *stream) {
-    if (c == nullptr) return fail(PSX_EINVAL, "psx_chunk_adam_step: ctx is NULL");
-    if (hyper == nullptr) return fail(PSX_EINVAL, "psx_chunk_adam_step: hyper is NULL");
-    if (n_chunks != 0 && chunks == nullptr) return fail(PSX_EINVAL, "psx_chunk_adam_step: chunks is NULL");
-    if (flags & ~(PSX_STEP_USE_FLAG | PSX_STEP_CHECK_FIRST | PSX_STEP_DEVICE_STATE)) return fail(PSX_EINVAL, "psx_chunk_adam_step: unknown flags 0x%x", flags);
-    const bool dev_state = (flags & PSX_STEP_DEVICE_STATE) != 0;
-    if (dev_state) {
-        if (!c->state_on) return fail(PSX_EINVAL, "psx_chunk_adam_step: PSX_STEP_DEVICE_STATE needs psx_step_state_init first");
-        const psx_adam_hyper &a = *hyper, &b = c->state_hyper;
-        if (a.lr != b.lr || a.beta1 != b.beta1 || a.beta2 != b.beta2 || a.eps != b.eps || a.weight_decay != b.weight_decay ||
-            (a.adamw_mode != 0) != (b.adamw_mode != 0))
-            return fail(PSX_EINVAL, "psx_chunk_adam_step: with PSX_STEP_DEVICE_STATE lr, betas, eps, weight_decay and adamw_mode must be "
-                                    "those given to psx_step_state_init (step and loss_scale are taken from the device)");
-    }
-    if (n_chunks > c->cfg.max_chunks)
-        return fail(PSX_ECAP, "psx_chunk_adam_step: %zu chunks, context holds %llu", n_chunks, (unsigned long long)c->cfg.max_chunks);
-    AdamScalars sc;
-    int32_t rc = prepare_adam_scalars(hyper, "psx_chunk_adam_step", &sc);
-    if (rc != PSX_OK) return rc;
-    const bool check_first = (flags & PSX_STEP_CHECK_FIRST) != 0;
-    const bool use_flag = check_first || (flags & PSX_STEP_USE_FLAG) != 0;
+// Everything that can be wrong with the chunk list is found here, before any work is enqueued.
+int32_t validate_step(psx_ctx *c, const psx_chunk *chunks, size_t n_chunks, bool dev_state, bool recording) {
     const uint64_t T = c->cfg.staging_tile_elems;
-    // a stream that is being recorded into a graph: only what replays as kernel launches on that one stream
-    const bool recording = capturing(static_cast<hipStream_t>(stream));
-    if (recording && !dev_state)
-        return fail(PSX_ECAPTURE, "psx_chunk_adam_step: a captured step would replay this call's t and loss scale for ever: use PSX_STEP_DEVICE_STATE");
-
-    // ---- validate everything before any work is enqueued
     for (size_t k = 0; k < n_chunks; k++) {
         const psx_chunk &ch = chunks[k];
         if (ch.loc_in > PSX_LOC_HOST || ch.loc_out > PSX_LOC_HOST)
@@ -914,51 +886,61 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
             }
         }
     }
-    if ((rc = set_device_guard(c)) != PSX_OK) return rc;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    const AdamScalars *sc_dev = dev_state ? &c->state_dev->sc : nullptr;
+    return PSX_OK;
+}
 
-    // ---- build the descriptor table: [resident | recast | check | spill tiles]
-    const uint64_t adam_tile = adam_tile_elems(c->tune);
-    const uint64_t recast_tile = kRecastTileElems;
+// What one call of psx_chunk_adam_step launches, derived from the chunk list: the sections of the run table
+// (in upload order: resident | re-cast | check | staged tiles | direct | direct re-cast) with their tile
+// counts, the byte counts of the part with a host side, and the launch shape of the kernels that work on
+// host memory.  The descriptors themselves are left in the context's scratch vectors.
+struct StepPlan {
+    uint64_t adam_tile = 0, recast_tile = 0;
+    uint64_t res_tiles = 0, res_elems = 0, recast_tiles = 0, check_tiles = 0;
+    size_t n_res = 0, n_recast = 0, n_check = 0;
+    uint64_t cpu_elems = 0, spill_elems = 0, h2d_bytes = 0, d2h_bytes = 0;
+    Tuning td;
+    size_t direct_off = 0, n_direct = 0, n_direct_recast = 0;
+    uint64_t direct_tiles = 0, direct_recast_tiles = 0, move_tiles = 0;
+};
+
+// Fills c->runs, c->moves, c->spill_tiles and c->cpu_tiles from the (validated) chunk list.
+void plan_step(psx_ctx *c, const psx_chunk *chunks, size_t n_chunks, bool use_flag, bool check_first, StepPlan &p) {
+    const uint64_t T = c->cfg.staging_tile_elems;
+    p.adam_tile = adam_tile_elems(c->tune);
+    p.recast_tile = kRecastTileElems;
     c->runs.clear();
-    uint64_t res_tiles = 0, res_elems = 0;
     for (size_t k = 0; k < n_chunks; k++) {
         const psx_chunk &ch = chunks[k];
         if (ch.used == 0 || ch.loc_in != PSX_LOC_HBM || ch.loc_out != PSX_LOC_HBM) continue;
-        res_tiles += push_run(c->runs, ch.g16, ch.p16, ch.p32, ch.m, ch.v, ch.used, res_tiles, adam_tile, (uint32_t)k);
-        res_elems += ch.used;
+        p.res_tiles += push_run(c->runs, ch.g16, ch.p16, ch.p32, ch.m, ch.v, ch.used, p.res_tiles, p.adam_tile, (uint32_t)k);
+        p.res_elems += ch.used;
     }
-    const size_t n_res = c->runs.size();
-    uint64_t recast_tiles = 0;
+    p.n_res = c->runs.size();
     if (use_flag)
         for (size_t k = 0; k < n_chunks; k++) {
             const psx_chunk &ch = chunks[k];
             if (ch.used == 0 || ch.loc_in != PSX_LOC_HBM || ch.loc_out != PSX_LOC_HBM || ch.g16 != ch.p16) continue;
-            recast_tiles += push_run(c->runs, ch.g16, ch.p16, ch.p32, ch.m, ch.v, ch.used, recast_tiles, recast_tile, (uint32_t)k);
+            p.recast_tiles += push_run(c->runs, ch.g16, ch.p16, ch.p32, ch.m, ch.v, ch.used, p.recast_tiles, p.recast_tile, (uint32_t)k);
         }
-    const size_t n_recast = c->runs.size() - n_res;
-    uint64_t check_tiles = 0;
+    p.n_recast = c->runs.size() - p.n_res;
     if (check_first)
         for (size_t k = 0; k < n_chunks; k++) {
             if (chunks[k].used == 0) continue;
-            check_tiles += push_run(c->runs, chunks[k].g16, nullptr, nullptr, nullptr, nullptr, chunks[k].used, check_tiles, kCheckTileElems, (uint32_t)k);
+            p.check_tiles += push_run(c->runs, chunks[k].g16, nullptr, nullptr, nullptr, nullptr, chunks[k].used, p.check_tiles, kCheckTileElems, (uint32_t)k);
         }
-    const size_t n_check = c->runs.size() - n_res - n_recast;
+    p.n_check = c->runs.size() - p.n_res - p.n_recast;
 
     std::vector<SpillTile> &tiles = c->spill_tiles;
     std::vector<CpuTile> &cpu_tiles = c->cpu_tiles;
     tiles.clear();
     cpu_tiles.clear();
-    uint64_t cpu_elems = 0;
-    uint64_t spill_elems = 0, h2d_bytes = 0, d2h_bytes = 0;
     uint64_t slot_counter = 0;
     const bool direct = c->tune.host_mode == 1;
     for (size_t k = 0; k < n_chunks; k++) {
         const psx_chunk &ch = chunks[k];
         if (ch.used == 0 || (ch.loc_in == PSX_LOC_HBM && ch.loc_out == PSX_LOC_HBM)) continue;
         const bool in_host = ch.loc_in == PSX_LOC_HOST, out_host = ch.loc_out == PSX_LOC_HOST;
-        if (ch.exec == PSX_EXEC_CPU) {                // updated by the host cores, see the end of this function
+        if (ch.exec == PSX_EXEC_CPU) {                // updated by the host cores: the last part of psx_chunk_adam_step
             const uint64_t ct = c->tune.cpu_tile_elems;
             for (uint64_t off = 0; off < ch.used; off += ct) {
                 CpuTile t;
@@ -971,13 +953,13 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
                 t.alias = ch.g16 == ch.p16;
                 cpu_tiles.push_back(t);
             }
-            cpu_elems += ch.used;
+            p.cpu_elems += ch.used;
             continue;
         }
-        spill_elems += ch.used;
+        p.spill_elems += ch.used;
         if (direct) {                                 // handled below: the kernels work on the host buffers
-            if (in_host) h2d_bytes += 3 * ch.used * sizeof(float);
-            if (out_host) d2h_bytes += 3 * ch.used * sizeof(float);
+            if (in_host) p.h2d_bytes += 3 * ch.used * sizeof(float);
+            if (out_host) p.d2h_bytes += 3 * ch.used * sizeof(float);
             continue;
         }
         for (uint64_t off = 0; off < ch.used; off += T) {
@@ -1001,30 +983,28 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
                 t.src[j] = in_host ? hs[j] + off : nullptr;
                 t.dst[j] = out_host ? const_cast<float *>(hs[j]) + off : nullptr;
             }
-            if (in_host) h2d_bytes += 3 * n * sizeof(float);
-            if (out_host) d2h_bytes += 3 * n * sizeof(float);
+            if (in_host) p.h2d_bytes += 3 * n * sizeof(float);
+            if (out_host) p.d2h_bytes += 3 * n * sizeof(float);
             t.run = c->runs.size();
             push_run(c->runs, static_cast<const uint16_t *>(ch.g16) + off, static_cast<uint16_t *>(ch.p16) + off,
-                     dev[0], dev[1], dev[2], n, 0, adam_tile, (uint32_t)k);
+                     dev[0], dev[1], dev[2], n, 0, p.adam_tile, (uint32_t)k);
             tiles.push_back(t);
         }
     }
     // host-resident chunks updated in place over the link: the kernel reads and writes pinned memory
-    Tuning td = c->tune;
-    td.adam_threads = 256; td.adam_unroll = c->tune.host_unroll; td.adam_wg_per_cu = 0;
-    td.grid_override = c->tune.host_grid;
-    const uint64_t direct_tile = adam_tile_elems(td);
-    const size_t direct_off = c->runs.size();
-    uint64_t direct_tiles = 0, direct_recast_tiles = 0, move_tiles = 0;
-    size_t n_direct = 0, n_direct_recast = 0;
+    p.td = c->tune;
+    p.td.adam_threads = 256; p.td.adam_unroll = c->tune.host_unroll; p.td.adam_wg_per_cu = 0;
+    p.td.grid_override = c->tune.host_grid;
+    const uint64_t direct_tile = adam_tile_elems(p.td);
+    p.direct_off = c->runs.size();
     c->moves.clear();
     if (direct) {
         for (size_t k = 0; k < n_chunks; k++) {
             const psx_chunk &ch = chunks[k];
             if (ch.used == 0 || ch.loc_in != PSX_LOC_HOST || ch.loc_out != PSX_LOC_HOST || ch.exec == PSX_EXEC_CPU) continue;
-            direct_tiles += push_run(c->runs, ch.g16, ch.p16, ch.p32_host, ch.m_host, ch.v_host, ch.used, direct_tiles, direct_tile, (uint32_t)k);
+            p.direct_tiles += push_run(c->runs, ch.g16, ch.p16, ch.p32_host, ch.m_host, ch.v_host, ch.used, p.direct_tiles, direct_tile, (uint32_t)k);
         }
-        n_direct = c->runs.size() - direct_off;
+        p.n_direct = c->runs.size() - p.direct_off;
         // chunks that change residence: read from the home they leave, written to the one they move to
         for (size_t k = 0; k < n_chunks; k++) {
             const psx_chunk &ch = chunks[k];
@@ -1039,9 +1019,9 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
             r.po = static_cast<float *>(in_host ? ch.p32 : ch.p32_host);
             r.mo = static_cast<float *>(in_host ? ch.m : ch.m_host);
             r.vo = static_cast<float *>(in_host ? ch.v : ch.v_host);
-            r.n = ch.used; r.tile_begin = move_tiles; r.chunk = (uint32_t)k;
+            r.n = ch.used; r.tile_begin = p.move_tiles; r.chunk = (uint32_t)k;
             c->moves.push_back(r);
-            move_tiles += (ch.used + kMoveTileElems - 1) / kMoveTileElems;
+            p.move_tiles += (ch.used + kMoveTileElems - 1) / kMoveTileElems;
         }
         // skipped step with the gradients in the fp16 parameter chunk: the parameters are cast back from
         // the home the states were read from (a skipped step leaves it valid)
@@ -1050,11 +1030,52 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
                 const psx_chunk &ch = chunks[k];
                 if (ch.used == 0 || (ch.loc_in == PSX_LOC_HBM && ch.loc_out == PSX_LOC_HBM) || ch.g16 != ch.p16 || ch.exec == PSX_EXEC_CPU) continue;
                 const bool in_host = ch.loc_in == PSX_LOC_HOST;
-                direct_recast_tiles += push_run(c->runs, ch.g16, ch.p16, in_host ? ch.p32_host : ch.p32, in_host ? ch.m_host : ch.m,
-                                                in_host ? ch.v_host : ch.v, ch.used, direct_recast_tiles, recast_tile, (uint32_t)k);
+                p.direct_recast_tiles += push_run(c->runs, ch.g16, ch.p16, in_host ? ch.p32_host : ch.p32, in_host ? ch.m_host : ch.m,
+                                                in_host ? ch.v_host : ch.v, ch.used, p.direct_recast_tiles, p.recast_tile, (uint32_t)k);
             }
-        n_direct_recast = c->runs.size() - direct_off - n_direct;
+        p.n_direct_recast = c->runs.size() - p.direct_off - p.n_direct;
     }
+}
+
+}  // namespace
+
+extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size_t n_chunks,
+                                       const psx_adam_hyper *hyper, uint32_t flags, void *stream) {
+    if (c == nullptr) return fail(PSX_EINVAL, "psx_chunk_adam_step: ctx is NULL");
+    if (hyper == nullptr) return fail(PSX_EINVAL, "psx_chunk_adam_step: hyper is NULL");
+    if (n_chunks != 0 && chunks == nullptr) return fail(PSX_EINVAL, "psx_chunk_adam_step: chunks is NULL");
+    if (flags & ~(PSX_STEP_USE_FLAG | PSX_STEP_CHECK_FIRST | PSX_STEP_DEVICE_STATE)) return fail(PSX_EINVAL, "psx_chunk_adam_step: unknown flags 0x%x", flags);
+    const bool dev_state = (flags & PSX_STEP_DEVICE_STATE) != 0;
+    if (dev_state) {
+        if (!c->state_on) return fail(PSX_EINVAL, "psx_chunk_adam_step: PSX_STEP_DEVICE_STATE needs psx_step_state_init first");
+        const psx_adam_hyper &a = *hyper, &b = c->state_hyper;
+        if (a.lr != b.lr || a.beta1 != b.beta1 || a.beta2 != b.beta2 || a.eps != b.eps || a.weight_decay != b.weight_decay ||
+            (a.adamw_mode != 0) != (b.adamw_mode != 0))
+            return fail(PSX_EINVAL, "psx_chunk_adam_step: with PSX_STEP_DEVICE_STATE lr, betas, eps, weight_decay and adamw_mode must be "
+                                    "those given to psx_step_state_init (step and loss_scale are taken from the device)");
+    }
+    if (n_chunks > c->cfg.max_chunks)
+        return fail(PSX_ECAP, "psx_chunk_adam_step: %zu chunks, context holds %llu", n_chunks, (unsigned long long)c->cfg.max_chunks);
+    AdamScalars sc;
+    int32_t rc = prepare_adam_scalars(hyper, "psx_chunk_adam_step", &sc);
+    if (rc != PSX_OK) return rc;
+    const bool check_first = (flags & PSX_STEP_CHECK_FIRST) != 0;
+    const bool use_flag = check_first || (flags & PSX_STEP_USE_FLAG) != 0;
+    // a stream that is being recorded into a graph: only what replays as kernel launches on that one stream
+    const bool recording = capturing(static_cast<hipStream_t>(stream));
+    if (recording && !dev_state)
+        return fail(PSX_ECAPTURE, "psx_chunk_adam_step: a captured step would replay this call's t and loss scale for ever: use PSX_STEP_DEVICE_STATE");
+
+    if ((rc = validate_step(c, chunks, n_chunks, dev_state, recording)) != PSX_OK) return rc;
+    if ((rc = set_device_guard(c)) != PSX_OK) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const AdamScalars *sc_dev = dev_state ? &c->state_dev->sc : nullptr;
+
+    // ---- descriptors of everything this call launches, then their upload (a no-op when nothing changed)
+    StepPlan pl;
+    plan_step(c, chunks, n_chunks, use_flag, check_first, pl);
+    std::vector<SpillTile> &tiles = c->spill_tiles;
+    std::vector<CpuTile> &cpu_tiles = c->cpu_tiles;
     if (c->runs.size() > 0xFFFFFFFFull) return fail(PSX_ECAP, "psx_chunk_adam_step: too many runs");
     const AdamRun *tbl = nullptr;
     const uint64_t *tbl_begins = nullptr;
@@ -1069,14 +1090,14 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
     if (check_first) {
         PSX_HIP(launch_fill_u32(c->flags_dev, c->flags_n, 0u, s));
         if ((rc = span_begin(c, c->t_check, s)) != PSX_OK) return rc;
-        PSX_HIP(launch_check(view(n_res + n_recast, n_check), check_tiles, c->flags_dev, c->flags_dev + 1, c->tune, c->n_cu, s));
+        PSX_HIP(launch_check(view(pl.n_res + pl.n_recast, pl.n_check), pl.check_tiles, c->flags_dev, c->flags_dev + 1, c->tune, c->n_cu, s));
         if ((rc = span_end(c, c->t_check, s)) != PSX_OK) return rc;
     }
 
     // ---- the side streams may start once earlier work on the caller's stream (and the check) is done
     const bool any_cpu = !cpu_tiles.empty();
     if (any_cpu && (rc = ensure_cpu(c)) != PSX_OK) return rc;
-    const bool any_side = !tiles.empty() || n_direct != 0 || move_tiles != 0 || any_cpu;
+    const bool any_side = !tiles.empty() || pl.n_direct != 0 || pl.move_tiles != 0 || any_cpu;
     c->t_spill.valid = false;
     if (any_side) {
         PSX_HIP(hipEventRecord(c->ev_entry, s));
@@ -1097,27 +1118,27 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
     bool any_h2d = false, any_d2h = false;
     auto enqueue = [&]() -> int32_t {
         // ---- HBM-resident chunks: one launch over all of them
-        c->adam_elems = res_elems;
+        c->adam_elems = pl.res_elems;
         c->t_adam.valid = false;
-        if (res_tiles != 0) {
+        if (pl.res_tiles != 0) {
             if ((rc = span_begin(c, c->t_adam, s)) != PSX_OK) return rc;
-            PSX_HIP(launch_adam(view(0, n_res), res_tiles, sc, flag, c->tune, c->n_cu, s, sc_dev));
+            PSX_HIP(launch_adam(view(0, pl.n_res), pl.res_tiles, sc, flag, c->tune, c->n_cu, s, sc_dev));
             if ((rc = span_end(c, c->t_adam, s)) != PSX_OK) return rc;
-            if (n_recast != 0)
-                PSX_HIP(launch_recast_if_flag(view(n_res, n_recast), recast_tiles, flag, c->tune, c->n_cu, s));
+            if (pl.n_recast != 0)
+                PSX_HIP(launch_recast_if_flag(view(pl.n_res, pl.n_recast), pl.recast_tiles, flag, c->tune, c->n_cu, s));
         }
 
         // ---- host-resident chunks, direct mode: one persistent launch on the side stream, concurrent with
         // the resident launch; every load and store of p/m/v crosses the host link once, in both directions at once
-        c->spill_elems = spill_elems; c->h2d_bytes = h2d_bytes; c->d2h_bytes = d2h_bytes;
-        if (n_direct != 0 || move_tiles != 0) {
-            if (n_direct != 0)
-                PSX_HIP(launch_adam(view(direct_off, n_direct), direct_tiles, sc, flag, td, c->n_cu, c->h2d, sc_dev));
-            if (move_tiles != 0)
-                PSX_HIP(launch_adam_move(MoveView{mtbl, mtbl_begins, (uint32_t)c->moves.size()}, move_tiles, sc, flag, c->tune,
+        c->spill_elems = pl.spill_elems; c->h2d_bytes = pl.h2d_bytes; c->d2h_bytes = pl.d2h_bytes;
+        if (pl.n_direct != 0 || pl.move_tiles != 0) {
+            if (pl.n_direct != 0)
+                PSX_HIP(launch_adam(view(pl.direct_off, pl.n_direct), pl.direct_tiles, sc, flag, pl.td, c->n_cu, c->h2d, sc_dev));
+            if (pl.move_tiles != 0)
+                PSX_HIP(launch_adam_move(MoveView{mtbl, mtbl_begins, (uint32_t)c->moves.size()}, pl.move_tiles, sc, flag, c->tune,
                                          (uint32_t)c->tune.host_grid, c->h2d, sc_dev));
-            if (n_direct_recast != 0)
-                PSX_HIP(launch_recast_if_flag(view(direct_off + n_direct, n_direct_recast), direct_recast_tiles, flag, td, c->n_cu, c->h2d));
+            if (pl.n_direct_recast != 0)
+                PSX_HIP(launch_recast_if_flag(view(pl.direct_off + pl.n_direct, pl.n_direct_recast), pl.direct_recast_tiles, flag, pl.td, c->n_cu, c->h2d));
             any_h2d = true;
         }
 
@@ -1136,9 +1157,9 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
                 any_h2d = true;
             }
             Tuning tn = c->tune;
-            PSX_HIP(launch_adam(view(t.run, 1), (t.n + adam_tile - 1) / adam_tile, sc, flag, tn, c->n_cu, s, sc_dev));
+            PSX_HIP(launch_adam(view(t.run, 1), (t.n + pl.adam_tile - 1) / pl.adam_tile, sc, flag, tn, c->n_cu, s, sc_dev));
             if (use_flag && t.alias)
-                PSX_HIP(launch_recast_if_flag(view(t.run, 1), (t.n + recast_tile - 1) / recast_tile, flag, tn, c->n_cu, s));
+                PSX_HIP(launch_recast_if_flag(view(t.run, 1), (t.n + pl.recast_tile - 1) / pl.recast_tile, flag, tn, c->n_cu, s));
             if (t.dst[0] != nullptr) {
                 PSX_HIP(hipEventRecord(c->ev_k[e], s));
                 PSX_HIP(hipStreamWaitEvent(c->d2h, c->ev_k[e], 0));
@@ -1152,7 +1173,7 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
         }
         // ---- host-resident chunks executed by the host cores: everything above is already running on the GPU;
         // this thread now pipelines  D2H fp16 gradient tile -> update of p/m/v in place -> H2D fp16 parameter tile
-        c->cpu_elems = cpu_elems;
+        c->cpu_elems = pl.cpu_elems;
         c->cpu_ms = 0.0f;
         if (any_cpu) {
             bool skip = false;
