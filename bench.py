@@ -67,6 +67,9 @@ def parse():
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="also launch psx_copy_bytes once over this many MiB (a plain copy of known size, "
                          "the yardstick the HBM traffic counters are scaled by)")
+    ap.add_argument("--fused-unpack", action="store_true",
+                    help="write the fp16 parameters to the tensors from inside the Adam launch (psx_chunk_adam_step_unpack) "
+                         "instead of a psx_unpack pass that reads the chunks back (all chunks must be HBM-resident)")
     ap.add_argument("--separate-check", action="store_true", help="run the overflow check as a pass of its own (2 B/element more) instead of inside the gradient pack")
     ap.add_argument("--staging-tile", type=int, default=4 << 20, help="elements per staging tile (host-resident chunks)")
     ap.add_argument("--staging-slots", type=int, default=3)
@@ -184,7 +187,7 @@ def setup(w, dev, host_fraction=0.0, staging_tile_elems=4 << 20, staging_slots=3
     return st
 
 
-def run_step(st, fused_check=False, new_loc=None):
+def run_step(st, fused_check=False, new_loc=None, fused_unpack=False):
     """One pass of the hot path; returns the overflow flag.  new_loc: where each chunk's fp32 states are
     to live after this step (default: where they are)."""
     from paper_2108_05818_amd import psx
@@ -217,8 +220,11 @@ def run_step(st, fused_check=False, new_loc=None):
         step_flags = psx.PSX_STEP_CHECK_FIRST                                 # a3 inside the step call
     hp = psx.make_hyper(lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps, weight_decay=w.weight_decay,
                         adamw_mode=w.adamw_mode, step=st.scaler.step, loss_scale=st.scaler.scale)
-    psx.psx_chunk_adam_step(ctx, st.chunks, hp, step_flags, n_chunks=st.nch)  # a4 / a5 / a6
-    psx.psx_unpack(ctx, psx.PSX_F16, st.o_ptrs, slots, st.p16, C, n=n)       # a2 (fp16 params back to tensors)
+    if fused_unpack:                                                           # a4 / a6 with a2's unpack inside the launch
+        psx.psx_chunk_adam_step_unpack(ctx, st.chunks, hp, step_flags, st.o_ptrs, slots, C, n_chunks=st.nch, n=n)
+    else:
+        psx.psx_chunk_adam_step(ctx, st.chunks, hp, step_flags, n_chunks=st.nch)  # a4 / a5 / a6
+        psx.psx_unpack(ctx, psx.PSX_F16, st.o_ptrs, slots, st.p16, C, n=n)       # a2 (fp16 params back to tensors)
     flag, _ = psx.psx_overflow_read(ctx)                                      # synchronises the stream
     psx.psx_loss_scale_update(st.scaler, flag)                                # a7
     return flag
@@ -415,7 +421,7 @@ def pick_workload(a):
     return w, host_fraction, plans, scaled_from
 
 
-def timed_steps(st, steps, warmup, fused_check, plans=None):
+def timed_steps(st, steps, warmup, fused_check, plans=None, fused_unpack=False):
     """`warmup` untimed steps, then exactly `steps` timed ones between two device synchronisations.
     Returns wall ms per step, the per-launch HIP-event times averaged over the timed steps, the link
     bytes summed over them, and the last step's psx_timing."""
@@ -424,7 +430,7 @@ def timed_steps(st, steps, warmup, fused_check, plans=None):
     psx.psx_ctx_set_profiling(st.ctx, 1)
     plan_at = (lambda t: plans[t]) if plans else (lambda t: None)
     for i in range(warmup):
-        run_step(st, fused_check, plan_at(1 + i))
+        run_step(st, fused_check, plan_at(1 + i), fused_unpack)
     torch.cuda.synchronize()
     phase = {"pack_ms": 0.0, "check_ms": 0.0, "adam_ms": 0.0, "unpack_ms": 0.0, "spill_ms": 0.0}
     link = {"h2d": 0, "d2h": 0, "min_h2d": 0, "min_d2h": 0, "moved_chunks": 0, "resident_chunks": []}
@@ -435,7 +441,7 @@ def timed_steps(st, steps, warmup, fused_check, plans=None):
     for i in range(steps):
         before = list(st.loc)
         ts = time.perf_counter()
-        skipped += run_step(st, fused_check, plan_at(1 + warmup + i))
+        skipped += run_step(st, fused_check, plan_at(1 + warmup + i), fused_unpack)
         each_step.append((time.perf_counter() - ts) * 1e3)   # the step ends with the flag read back: the stream is drained
         tm = psx.psx_ctx_get_timing(st.ctx)      # events of this step
         each_adam.append(tm.adam_ms)
@@ -485,14 +491,16 @@ def plain_copy_rate(ctx, dev):
     return 10 * 2 * nb / (e0.elapsed_time(e1) * 1e-3) / 1e9
 
 
-def adam_roofline(r, copy_gbs=None):
+def adam_roofline(r, copy_gbs=None, bytes_per_elem=ADAM_BYTES_PER_ELEM):
     """HBM roofline of the resident Adam launch from the HIP-event times of `timed_steps`."""
     adam_elems = int(r["tm"].adam_elems)
-    adam_bytes = ADAM_BYTES_PER_ELEM * adam_elems
+    adam_bytes = bytes_per_elem * adam_elems
     ms = r["phase"]["adam_ms"]
     achieved = adam_bytes / (ms * 1e-3) / 1e9 if ms > 0 else 0.0
     out = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-           "kernel": "psx::adam_kernel (resident chunks, one launch)", "bytes_per_launch": adam_bytes, "avg_launch_ms": ms,
+           "kernel": ("psx::adam_out_kernel (resident chunks and the fp16 tensors, one launch)" if bytes_per_elem != ADAM_BYTES_PER_ELEM
+                      else "psx::adam_kernel (resident chunks, one launch)"),
+           "bytes_per_launch": adam_bytes, "avg_launch_ms": ms,
            "launch_ms": r.get("adam_launch_ms")}
     if copy_gbs:
         out.update(same_run_plain_copy_GBs=copy_gbs, frac_of_plain_copy=achieved / copy_gbs)
@@ -553,6 +561,17 @@ def leg_chunk_reuse(st):
     r = timed_steps(st, 10, 3, True)
     return {"workload": w.name, "steps": 10, "warmup": 3, "ms_per_step": r["ms"], "gelem_s": w.n_elems / (r["ms"] * 1e-3) / 1e9,
             "bytes_of_chunk_lists_per_param": 14, "roofline": adam_roofline(r)}
+
+
+def leg_fused_unpack(st):
+    """The headline step on the headline's own buffers with the fp16 parameters written to the tensors from
+    inside the Adam launch (psx_chunk_adam_step_unpack) instead of a psx_unpack pass that reads the chunks
+    back: 4 + 30 bytes per element in two launches instead of 4 + 28 + 4 in three."""
+    w = st.w
+    r = timed_steps(st, 10, 3, True, fused_unpack=True)
+    return {"workload": w.name, "steps": 10, "warmup": 3, "ms_per_step": r["ms"], "gelem_s": w.n_elems / (r["ms"] * 1e-3) / 1e9,
+            "bytes_per_elem_of_the_step": 34, "phase_ms": r["phase"],
+            "roofline": adam_roofline(r, bytes_per_elem=ADAM_BYTES_PER_ELEM + 2)}
 
 
 def placement_trials(a, dev, n):
@@ -711,7 +730,7 @@ def main():
     w, host_fraction, plans, scaled_from = pick_workload(a)
     # the default run (headline workload, no overrides) appends the other halves of the metric as legs
     headline = (a.workload == "gpt1b" and not a.layers and not a.chunk_elems and host_fraction == 0
-                and not a.chunk_reuse and not a.tune and not a.arena_skew and not a.one_arena)
+                and not a.chunk_reuse and not a.tune and not a.arena_skew and not a.one_arena and not a.fused_unpack)
     legs = headline and not a.no_legs
     # the fp32 source tensors are needed again only by the oracle leg, and only the first few of them
     st = setup(w, dev, host_fraction, a.staging_tile, a.staging_slots,
@@ -743,7 +762,7 @@ def main():
     if not a.no_cpu_baseline:
         cpu = cpu_baseline(st)
 
-    r = timed_steps(st, a.steps, a.warmup, not a.separate_check, plans)
+    r = timed_steps(st, a.steps, a.warmup, not a.separate_check, plans, a.fused_unpack)
     ms, phase, tm = r["ms"], r["phase"], r["tm"]
     on_device = None
     if a.device_state or a.graph:
@@ -753,7 +772,8 @@ def main():
                      "gelem_s": w.n_elems / (rd["ms"] * 1e-3) / 1e9, "steps_skipped": rd["skipped"]}
     n_elems = w.n_elems
     copy_gbs = plain_copy_rate(st.ctx, dev)
-    roofline = adam_roofline(r, copy_gbs)
+    # with the unpack fused in, the launch also writes the fp16 parameters to the tensors: 2 B/element more
+    roofline = adam_roofline(r, copy_gbs, ADAM_BYTES_PER_ELEM + (2 if a.fused_unpack else 0))
     traffic_file = os.path.join("profiles", "adam_kernel_gpt1b_hbm_traffic.txt")
     roofline["traffic"] = read_traffic(os.path.join(ROOT, traffic_file)) if headline else None
     # not a quantity of this run: HBM bytes per launch from the committed FETCH_SIZE / WRITE_SIZE counter runs
@@ -770,7 +790,7 @@ def main():
                    "chunk_elems": w.chunk_elems,
                    "n_chunks": st.nch, "host_resident_chunks": st.n_host, "host_chunks_on_host_cores": st.n_cpu,
                    "loss_scale": w.loss_scale,
-                   "weight_decay": w.weight_decay, "fused_check": not a.separate_check, "chunk_reuse": a.chunk_reuse,
+                   "weight_decay": w.weight_decay, "fused_check": not a.separate_check, "fused_unpack": a.fused_unpack, "chunk_reuse": a.chunk_reuse,
                    "skipped_steps": r["skipped"]},
         "roofline": roofline,
         "adam_only_gelem_s": adam_elems / (phase["adam_ms"] * 1e-3) / 1e9 if phase["adam_ms"] > 0 else None,
@@ -788,6 +808,7 @@ def main():
     if legs:
         # the other halves of the metric, each a short run of its own after the timed headline:
         # the paper's chunk-reuse layout, host-resident chunks over the link, and on the host cores
+        out["fused_unpack"] = leg_fused_unpack(st)
         out["chunk_reuse"] = leg_chunk_reuse(st)
     release(st)
     if a.placements:

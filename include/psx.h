@@ -268,6 +268,27 @@ int32_t psx_chunk_adam_step(psx_ctx *ctx, const psx_chunk *chunks, size_t n_chun
 int32_t psx_adam_step_scalars(const psx_adam_hyper *hyper, float *out);
 
 /*
+ * psx_chunk_adam_step with the fp16 parameter unpack fused in (Sec. "Training Stage", last paragraph: the
+ * updated parameters reach the param fp16 chunk; a framework whose fp16 parameter tensors are not views
+ * into that chunk needs them copied out, which psx_unpack does by reading the chunk again).  Here the
+ * kernel that produces fp16(p32) stores it twice, into chunk.p16 and into the tensor that owns the
+ * position, so the chunk is not read back: 30 bytes per element in one launch instead of 28 + 4 in two.
+ *   p16_tensors[n_tensors]  host array of device pointers (fp16, element-aligned); slots[n_tensors] as
+ *                           returned by psx_chunk_layout for chunk_elems.  Slots must not overlap;
+ *                           elements of the chunk list that no slot covers are written to the chunk only.
+ * Every chunk with used > 0 must stay in HBM (loc_in == loc_out == PSX_LOC_HBM, PSX_EXEC_GPU) and the Adam
+ * launch shape must be the default one, else PSX_EINVAL.  Elements of a slot behind its chunk's `used`
+ * are not written.  On a skipped step (overflow flag set) no tensor is written: they keep the parameters
+ * of the last applied step, which are the ones the chunk list holds.  Flags, errors, streams and graph
+ * capture as for psx_chunk_adam_step; results are bit-identical to psx_chunk_adam_step followed by
+ * psx_unpack(PSX_F16) of the p16 chunks.
+ */
+int32_t psx_chunk_adam_step_unpack(psx_ctx *ctx, const psx_chunk *chunks, size_t n_chunks,
+                                   const psx_adam_hyper *hyper, uint32_t flags,
+                                   void *const *p16_tensors, const psx_slot *slots, size_t n_tensors,
+                                   uint64_t chunk_elems, void *stream);
+
+/*
  * The same step for callers that cannot allocate: code under HIP graph capture, tight serving loops,
  * harnesses that forbid hipMalloc.  No context: the overflow flags and the descriptor tables the kernels
  * search live in one static device array of PSX_NOALLOC_SCRATCH_BYTES that every GPU the library runs on

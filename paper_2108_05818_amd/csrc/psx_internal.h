@@ -137,6 +137,19 @@ struct MoveView {
     const uint64_t *begins;
     uint32_t n;
 };
+// One fp16 output range of the fused parameter unpack: elements [off, off + n) of a chunk go to dst[0, n).
+struct OutSeg {
+    uint16_t *dst;
+    uint64_t off, n;
+    uint64_t pad;
+};
+static_assert(sizeof(OutSeg) == 32, "descriptor size");
+// The output ranges of every run of a RunView: those of run r are segs[first[r] .. first[r + 1]), ascending
+// in `off` and disjoint (first has one entry more than there are runs).
+struct OutView {
+    const OutSeg *segs;
+    const uint32_t *first;
+};
 struct SegView {
     const CopySeg *segs;
     const uint64_t *begins;
@@ -157,6 +170,11 @@ int query_lds_per_cu(int device);
 hipError_t launch_adam(const RunView &rv, uint64_t n_tiles,
                        const AdamScalars &sc, const uint32_t *flag_dev, const Tuning &t,
                        int n_cu, hipStream_t s, const AdamScalars *sc_dev = nullptr);
+// The same update with the fp16 parameters written a second time, to the ranges of `out` (the tensors'
+// own memory): psx_unpack without reading the chunk back.  Fixed launch shape: one wavefront per workgroup
+// and tile of 256 elements; the runs' tile_begin must count tiles of that size.
+hipError_t launch_adam_out(const RunView &rv, uint64_t n_tiles, const AdamScalars &sc, const uint32_t *flag_dev,
+                           const Tuning &t, int n_cu, hipStream_t s, const AdamScalars *sc_dev, const OutView &out);
 // Same update for runs that change residence, on `grid` persistent workgroups.  With *flag_dev != 0
 // the states are copied to their new home unchanged and p16 is left alone.
 hipError_t launch_adam_move(const MoveView &mv, uint64_t n_tiles, const AdamScalars &sc,

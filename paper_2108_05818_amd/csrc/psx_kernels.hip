@@ -243,6 +243,147 @@ hipError_t launch_adam(const RunView &rv, uint64_t n_tiles, const AdamScalars &s
               : launch_adam_u<256, false>(t.adam_unroll, rv, n_tiles, sc, sc_dev, flag, grid, lds, s);
 }
 
+// ------------------------------------------------------------------ Adam with the fp16 unpack fused in
+// adam_kernel's update (one wavefront, one tile of 256 elements, one row) that stores the fp16 parameters
+// twice: into the param fp16 chunk and into the tensors' own memory, found through the run's output
+// ranges.  A tile that lies inside one range takes one more 8-byte store per lane (shifted across lanes
+// first if the destination is off the 8-byte grid); a tile that spans tensors writes its elements one by
+// one, each lane walking on from the tile's first range.
+__device__ __forceinline__ void scatter_f16(const OutSeg *__restrict__ segs, uint32_t s, uint32_t s_end,
+                                            uint64_t e0, uint32_t cnt, const _Float16 *vals) {
+    for (uint32_t k = 0; k < cnt; k++) {
+        const uint64_t e = e0 + k;
+        while (s < s_end && e >= segs[s].off + segs[s].n) s++;
+        if (s < s_end && e >= segs[s].off) *gptr<_Float16>(segs[s].dst + (e - segs[s].off)) = vals[k];
+    }
+}
+
+template <bool NT, int DM>
+__global__ __launch_bounds__(64) void adam_out_kernel(const AdamRun *__restrict__ runs,
+                                                      const uint64_t *__restrict__ begins,
+                                                      uint32_t n_runs, uint64_t n_tiles,
+                                                      AdamScalars sc,
+                                                      const AdamScalars *__restrict__ sc_dev,
+                                                      const uint32_t *__restrict__ flag,
+                                                      const OutSeg *__restrict__ segs,
+                                                      const uint32_t *__restrict__ first) {
+    if (flag != nullptr && *flag != 0) return;          // overflow: nothing is updated and nothing is written
+    if (sc_dev != nullptr) sc = *sc_dev;
+    constexpr uint32_t TILE = 256;
+    const uint32_t tid = threadIdx.x;
+    for (uint64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const uint32_t r = find_owner(begins, n_runs, tile);
+        const uint16_t *g16 = runs[r].g16;
+        uint16_t *p16 = runs[r].p16;
+        float *pp = runs[r].p, *pm = runs[r].m, *pv = runs[r].v;
+        const uint64_t n = runs[r].n;
+        const uint64_t base = (tile - runs[r].tile_begin) * TILE;
+        // the first output range of this run that ends behind the tile's first element (uniform: scalar loads)
+        const uint32_t s_end = first[r + 1];
+        uint32_t lo = first[r], hi = s_end;
+        while (lo < hi) {
+            const uint32_t mid = lo + ((hi - lo) >> 1);
+            if (segs[mid].off + segs[mid].n > base) hi = mid;
+            else lo = mid + 1;
+        }
+        const uint32_t s0 = lo;
+        const uint64_t i = base + tid * 4;
+        if (n - base >= TILE) {
+            const f16x4 g = ld<NT>(gptr<f16x4>(g16 + i));
+            f32x4 p = ld<NT>(gptr<f32x4>(pp + i));
+            f32x4 m = ld<NT>(gptr<f32x4>(pm + i));
+            f32x4 v = ld<NT>(gptr<f32x4>(pv + i));
+            f16x4 h;
+#pragma unroll
+            for (int k = 0; k < 4; k++) {
+                float pk = p[k], mk = m[k], vk = v[k];
+                adam_elem<DM>((float)g[k], pk, mk, vk, sc);
+                p[k] = pk; m[k] = mk; v[k] = vk;
+                h[k] = (_Float16)pk;
+            }
+            st<NT>(gptr<f32x4>(pp + i), p);
+            st<NT>(gptr<f32x4>(pm + i), m);
+            st<NT>(gptr<f32x4>(pv + i), v);
+            st<NT>(gptr<f16x4>(p16 + i), h);
+            uint16_t *dst = nullptr;                    // where the tile's first element goes, if one range holds the whole tile
+            if (s0 < s_end) {
+                const uint64_t off = segs[s0].off, cnt = segs[s0].n;
+                if (off <= base && base + TILE <= off + cnt) dst = segs[s0].dst + (base - off);
+            }
+            if (dst != nullptr) {
+                const uint32_t a = (4u - ((uint32_t)(reinterpret_cast<uintptr_t>(dst) >> 1) & 3u)) & 3u;   // elements up to the first 8-byte boundary
+                if (a == 0) {
+                    st<NT>(gptr<f16x4>(dst + tid * 4), h);
+                } else {
+                    // The destination is off by a elements (uniform for the tile): the 8-byte word behind the
+                    // boundary in front of lane j's last 4 - a elements is made of those and of the first a
+                    // elements of lane j + 1, handed over by a wavefront shift.  Lane 0 also writes the a
+                    // elements in front of the first boundary, lane 63 its last 4 - a, one by one.
+                    const u16x4 hb = __builtin_bit_cast(u16x4, h);
+                    const uint32_t w0 = (uint32_t)hb[0] | ((uint32_t)hb[1] << 16), w1 = (uint32_t)hb[2] | ((uint32_t)hb[3] << 16);
+                    const uint32_t n0 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w0, 0x130, 0xf, 0xf, false);
+                    const uint32_t n1 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w1, 0x130, 0xf, 0xf, false);
+                    uint32_t o0, o1;
+                    if (a == 1) { o0 = __builtin_amdgcn_alignbyte(w1, w0, 2); o1 = __builtin_amdgcn_alignbyte(n0, w1, 2); }
+                    else if (a == 2) { o0 = w1; o1 = n0; }
+                    else { o0 = __builtin_amdgcn_alignbyte(n0, w1, 2); o1 = __builtin_amdgcn_alignbyte(n1, n0, 2); }
+                    uint16_t *mine = dst + tid * 4;
+                    if (tid != 63) {
+                        typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+                        const u32x2 word = {o0, o1};
+                        st<NT>(gptr<u32x2>(mine + a), word);
+                    } else {
+                        for (uint32_t k = a; k < 4; k++) *gptr<uint16_t>(mine + k) = hb[k];
+                    }
+                    if (tid == 0)
+                        for (uint32_t k = 0; k < a; k++) *gptr<uint16_t>(mine + k) = hb[k];
+                }
+            } else {
+                const _Float16 vals[4] = {h[0], h[1], h[2], h[3]};
+                scatter_f16(segs, s0, s_end, i, 4, vals);
+            }
+        } else if (i < n) {
+            // last, partial tile of a run: element by element
+            const uint32_t cnt = n - i < 4 ? (uint32_t)(n - i) : 4u;
+            _Float16 vals[4];
+            for (uint32_t k = 0; k < cnt; k++) {
+                float pk = *gptr<float>(pp + i + k), mk = *gptr<float>(pm + i + k), vk = *gptr<float>(pv + i + k);
+                const _Float16 gk = *gptr<_Float16>(g16 + i + k);
+                adam_elem<DM>((float)gk, pk, mk, vk, sc);
+                *gptr<float>(pp + i + k) = pk; *gptr<float>(pm + i + k) = mk; *gptr<float>(pv + i + k) = vk;
+                vals[k] = (_Float16)pk;
+                *gptr<_Float16>(p16 + i + k) = vals[k];
+            }
+            scatter_f16(segs, s0, s_end, i, cnt, vals);
+        }
+    }
+}
+
+hipError_t launch_adam_out(const RunView &rv, uint64_t n_tiles, const AdamScalars &sc, const uint32_t *flag,
+                           const Tuning &t, int n_cu, hipStream_t s, const AdamScalars *sc_dev, const OutView &out) {
+    if (n_tiles == 0) return hipSuccess;
+    const uint32_t grid = grid_for(n_tiles, t.adam_blocks_per_cu, n_cu);
+    const uint32_t lds = throttle_lds(t.adam_wg_per_cu, t.lds_per_cu);
+#define PSX_LAUNCH_OUT(NT_, DM_)                                                                                   \
+    hipLaunchKernelGGL((adam_out_kernel<NT_, DM_>), dim3(grid), dim3(64), lds, s, rv.runs, rv.begins, rv.n, n_tiles, \
+                       sc, sc_dev, flag, out.segs, out.first)
+    if (t.nontemporal != 0) {
+        switch (sc.decay_mode) {
+            case 0: PSX_LAUNCH_OUT(true, 0); break;
+            case 1: PSX_LAUNCH_OUT(true, 1); break;
+            default: PSX_LAUNCH_OUT(true, 2); break;
+        }
+    } else {
+        switch (sc.decay_mode) {
+            case 0: PSX_LAUNCH_OUT(false, 0); break;
+            case 1: PSX_LAUNCH_OUT(false, 1); break;
+            default: PSX_LAUNCH_OUT(false, 2); break;
+        }
+    }
+#undef PSX_LAUNCH_OUT
+    return hipGetLastError();
+}
+
 // ------------------------------------------------------------------ Adam on runs that change residence
 // The fp32 states are read from the home they leave and written to the home
 // they move to, so each crosses the host link once and no copy comes before or

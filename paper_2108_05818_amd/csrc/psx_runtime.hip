@@ -3,6 +3,7 @@
 // HBM-resident chunks and, for host-resident chunks, a launch that works on the
 // pinned buffers over the link, a staged H2D / update / D2H pipeline, or the
 // host cores (fp16 tiles copied out and in around an in-place host update).
+#include <algorithm>
 #include <chrono>
 #include <cmath>
 #include <cstring>
@@ -187,7 +188,7 @@ struct psx_ctx {
     int n_cu = 0;
     psx_ctx_config cfg{};
     Tuning tune;
-    Table adam_tbl, move_tbl, check_tbl, pack_tbl, unpack_tbl;
+    Table adam_tbl, move_tbl, check_tbl, pack_tbl, unpack_tbl, out_tbl;
     uint32_t *flags_dev = nullptr;     // [0] global, [1 + c] chunk c
     uint32_t *flags_host = nullptr;    // pinned read-back buffer
     size_t flags_n = 0;
@@ -201,6 +202,8 @@ struct psx_ctx {
     std::vector<AdamRun> runs;         // scratch for table building
     std::vector<MoveRun> moves;
     std::vector<CopySeg> segs;
+    std::vector<OutSeg> outs;          // output ranges of the fused fp16 unpack, sorted by (chunk, offset)
+    std::vector<uint32_t> out_first;   // per resident run: index of its first range (one entry more than runs)
     std::vector<unsigned char> blob;   // scratch: descriptors + first tiles, as uploaded
     std::vector<SpillTile> spill_tiles;   // scratch of psx_chunk_adam_step (kept to keep their capacity)
     std::vector<CpuTile> cpu_tiles;
@@ -332,7 +335,7 @@ extern "C" int32_t psx_ctx_destroy(psx_ctx *c) {
         if (e != hipSuccess && rc == PSX_OK) rc = fail(PSX_EHIP, "psx_ctx_destroy: %s -> %s", what, hipGetErrorString(e));
     };
     note(hipDeviceSynchronize(), "hipDeviceSynchronize");
-    for (Table *t : {&c->adam_tbl, &c->move_tbl, &c->check_tbl, &c->pack_tbl, &c->unpack_tbl}) {
+    for (Table *t : {&c->adam_tbl, &c->move_tbl, &c->check_tbl, &c->pack_tbl, &c->unpack_tbl, &c->out_tbl}) {
         int32_t r = table_free(*t);
         if (r != PSX_OK && rc == PSX_OK) rc = r;
     }
@@ -1037,10 +1040,120 @@ void plan_step(psx_ctx *c, const psx_chunk *chunks, size_t n_chunks, bool use_fl
     }
 }
 
+// Where psx_chunk_adam_step_unpack is to leave the fp16 parameters besides the chunk list.
+struct OutSpec {
+    void *const *tensors;
+    const psx_slot *slots;
+    size_t n;
+    uint64_t chunk_elems;
+};
+
+// The fused unpack runs inside the resident launch at its default shape: every chunk must stay in HBM.
+int32_t validate_out(psx_ctx *c, const psx_chunk *chunks, size_t n_chunks, const OutSpec &o) {
+    const char *who = "psx_chunk_adam_step_unpack";
+    if (o.chunk_elems == 0) return fail(PSX_EINVAL, "%s: chunk_elems is 0", who);
+    if (o.n != 0 && (o.tensors == nullptr || o.slots == nullptr)) return fail(PSX_EINVAL, "%s: tensors/slots is NULL", who);
+    if (o.n > c->cfg.max_tensors) return fail(PSX_ECAP, "%s: %zu tensors, context holds %llu", who, o.n, (unsigned long long)c->cfg.max_tensors);
+    if (c->tune.adam_threads != 64 || c->tune.adam_unroll != 1)
+        return fail(PSX_EINVAL, "%s: runs at the default launch shape only (PSX_TUNE_ADAM_THREADS 64, PSX_TUNE_ADAM_UNROLL 1)", who);
+    for (size_t k = 0; k < n_chunks; k++) {
+        const psx_chunk &ch = chunks[k];
+        if (ch.used == 0) continue;
+        if (ch.loc_in != PSX_LOC_HBM || ch.loc_out != PSX_LOC_HBM || ch.exec != PSX_EXEC_GPU)
+            return fail(PSX_EINVAL, "%s: chunk %zu: only chunks that stay in HBM and are updated by the GPU", who, k);
+        if (ch.used > o.chunk_elems) return fail(PSX_EINVAL, "%s: chunk %zu uses more than chunk_elems elements", who, k);
+    }
+    const uint64_t total = (uint64_t)n_chunks * o.chunk_elems;
+    for (size_t i = 0; i < o.n; i++) {
+        const uint64_t sz = o.slots[i].numel;
+        if (sz == 0) continue;
+        if (o.tensors[i] == nullptr) return fail(PSX_EINVAL, "%s: tensor %zu is NULL", who, i);
+        if (reinterpret_cast<uintptr_t>(o.tensors[i]) % 2) return fail(PSX_EALIGN, "%s: tensor %zu is not element-aligned", who, i);
+        if (o.slots[i].offset > o.chunk_elems) return fail(PSX_EINVAL, "%s: slot %zu offset beyond the chunk", who, i);
+        const uint64_t lin = (uint64_t)o.slots[i].chunk * o.chunk_elems + o.slots[i].offset;
+        if (lin > total || sz > total - lin)
+            return fail(PSX_EINVAL, "%s: slot %zu (chunk %u offset %llu numel %llu) runs past the chunk list", who, i,
+                        o.slots[i].chunk, (unsigned long long)o.slots[i].offset, (unsigned long long)sz);
+    }
+    return PSX_OK;
+}
+
+// Cuts every tensor into its pieces per chunk, keeps what lies inside the chunk's used prefix (the update
+// produces nothing behind it), orders the pieces by chunk and offset and refuses overlapping ones; then
+// notes for each resident run (c->runs[0 .. n_res), ascending in chunk) where its pieces start.
+int32_t build_out(psx_ctx *c, const psx_chunk *chunks, size_t n_chunks, const OutSpec &o, size_t n_res) {
+    (void)n_chunks;
+    c->outs.clear();
+    for (size_t i = 0; i < o.n; i++) {
+        const uint64_t sz = o.slots[i].numel;
+        const uint64_t lin = (uint64_t)o.slots[i].chunk * o.chunk_elems + o.slots[i].offset;
+        uint64_t done = 0;
+        while (done < sz) {
+            const uint64_t p = lin + done;
+            const uint64_t ck = p / o.chunk_elems, off = p % o.chunk_elems;
+            const uint64_t take = sz - done < o.chunk_elems - off ? sz - done : o.chunk_elems - off;
+            const uint64_t used = chunks[ck].used;
+            if (off < used) {
+                OutSeg g;
+                g.dst = static_cast<uint16_t *>(o.tensors[i]) + done;
+                g.off = off;
+                g.n = take < used - off ? take : used - off;
+                g.pad = ck;                             // the chunk, for the ordering below; the kernel does not read it
+                c->outs.push_back(g);
+            }
+            done += take;
+        }
+    }
+    std::stable_sort(c->outs.begin(), c->outs.end(),
+                     [](const OutSeg &a, const OutSeg &b) { return a.pad != b.pad ? a.pad < b.pad : a.off < b.off; });
+    for (size_t j = 1; j < c->outs.size(); j++)
+        if (c->outs[j].pad == c->outs[j - 1].pad && c->outs[j].off < c->outs[j - 1].off + c->outs[j - 1].n)
+            return fail(PSX_EINVAL, "psx_chunk_adam_step_unpack: two slots overlap in chunk %llu", (unsigned long long)c->outs[j].pad);
+    if (c->outs.size() > 0xFFFFFFFFull) return fail(PSX_ECAP, "psx_chunk_adam_step_unpack: too many output ranges");
+    c->out_first.assign(n_res + 1, (uint32_t)c->outs.size());
+    size_t j = 0;
+    for (size_t r = 0; r < n_res; r++) {
+        while (j < c->outs.size() && c->outs[j].pad < c->runs[r].chunk) j++;
+        c->out_first[r] = (uint32_t)j;
+    }
+    return PSX_OK;
+}
+
+int32_t upload_out(psx_ctx *c, hipStream_t s, OutView *view) {
+    const size_t nd = c->outs.size() * sizeof(OutSeg), nf = c->out_first.size() * sizeof(uint32_t);
+    c->blob.resize(nd + nf);
+    if (nd) memcpy(c->blob.data(), c->outs.data(), nd);
+    memcpy(c->blob.data() + nd, c->out_first.data(), nf);
+    const int32_t rc = table_upload(c->out_tbl, c->blob.data(), c->blob.size(), s);
+    if (rc != PSX_OK) return rc;
+    const unsigned char *base = static_cast<const unsigned char *>(c->out_tbl.dev);
+    view->segs = reinterpret_cast<const OutSeg *>(base);
+    view->first = reinterpret_cast<const uint32_t *>(base + nd);
+    return PSX_OK;
+}
+
+int32_t adam_step_impl(psx_ctx *c, const psx_chunk *chunks, size_t n_chunks, const psx_adam_hyper *hyper, uint32_t flags,
+                       void *stream, const OutSpec *out);
+
 }  // namespace
 
 extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size_t n_chunks,
                                        const psx_adam_hyper *hyper, uint32_t flags, void *stream) {
+    return adam_step_impl(c, chunks, n_chunks, hyper, flags, stream, nullptr);
+}
+
+extern "C" int32_t psx_chunk_adam_step_unpack(psx_ctx *c, const psx_chunk *chunks, size_t n_chunks,
+                                              const psx_adam_hyper *hyper, uint32_t flags,
+                                              void *const *p16_tensors, const psx_slot *slots, size_t n_tensors,
+                                              uint64_t chunk_elems, void *stream) {
+    const OutSpec out{p16_tensors, slots, n_tensors, chunk_elems};
+    return adam_step_impl(c, chunks, n_chunks, hyper, flags, stream, &out);
+}
+
+namespace {
+
+int32_t adam_step_impl(psx_ctx *c, const psx_chunk *chunks, size_t n_chunks, const psx_adam_hyper *hyper, uint32_t flags,
+                       void *stream, const OutSpec *out) {
     if (c == nullptr) return fail(PSX_EINVAL, "psx_chunk_adam_step: ctx is NULL");
     if (hyper == nullptr) return fail(PSX_EINVAL, "psx_chunk_adam_step: hyper is NULL");
     if (n_chunks != 0 && chunks == nullptr) return fail(PSX_EINVAL, "psx_chunk_adam_step: chunks is NULL");
@@ -1067,6 +1180,7 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
         return fail(PSX_ECAPTURE, "psx_chunk_adam_step: a captured step would replay this call's t and loss scale for ever: use PSX_STEP_DEVICE_STATE");
 
     if ((rc = validate_step(c, chunks, n_chunks, dev_state, recording)) != PSX_OK) return rc;
+    if (out != nullptr && (rc = validate_out(c, chunks, n_chunks, *out)) != PSX_OK) return rc;
     if ((rc = set_device_guard(c)) != PSX_OK) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const AdamScalars *sc_dev = dev_state ? &c->state_dev->sc : nullptr;
@@ -1085,6 +1199,11 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
     if (!c->moves.empty() && (rc = upload_described(c->move_tbl, c->moves, c->blob, s, &mtbl, &mtbl_begins)) != PSX_OK) return rc;
     auto view = [&](size_t off, size_t n) { return RunView{tbl + off, tbl_begins + off, (uint32_t)n}; };
     const uint32_t *flag = use_flag ? c->flags_dev : nullptr;
+    OutView out_view{nullptr, nullptr};
+    if (out != nullptr) {
+        if ((rc = build_out(c, chunks, n_chunks, *out, pl.n_res)) != PSX_OK) return rc;
+        if ((rc = upload_out(c, s, &out_view)) != PSX_OK) return rc;
+    }
 
     // ---- overflow check over every gradient chunk
     if (check_first) {
@@ -1122,7 +1241,8 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
         c->t_adam.valid = false;
         if (pl.res_tiles != 0) {
             if ((rc = span_begin(c, c->t_adam, s)) != PSX_OK) return rc;
-            PSX_HIP(launch_adam(view(0, pl.n_res), pl.res_tiles, sc, flag, c->tune, c->n_cu, s, sc_dev));
+            if (out != nullptr) PSX_HIP(launch_adam_out(view(0, pl.n_res), pl.res_tiles, sc, flag, c->tune, c->n_cu, s, sc_dev, out_view));
+            else PSX_HIP(launch_adam(view(0, pl.n_res), pl.res_tiles, sc, flag, c->tune, c->n_cu, s, sc_dev));
             if ((rc = span_end(c, c->t_adam, s)) != PSX_OK) return rc;
             if (pl.n_recast != 0)
                 PSX_HIP(launch_recast_if_flag(view(pl.n_res, pl.n_recast), pl.recast_tiles, flag, c->tune, c->n_cu, s));
@@ -1241,3 +1361,5 @@ extern "C" int32_t psx_chunk_adam_step(psx_ctx *c, const psx_chunk *chunks, size
     }
     return rc_enqueue;
 }
+
+}  // namespace

@@ -32,7 +32,7 @@ EXPORTS = [
     "psx_loss_scale_update", "psx_ctx_set_tuning", "psx_ctx_set_profiling", "psx_ctx_get_timing",
     "psx_copy_bytes", "psx_measure_link", "psx_pinned_alloc", "psx_pinned_free", "psx_plan_residency",
     "psx_chunk_size_search", "psx_chunk_adam_step_noalloc", "psx_adam_step_scalars",
-    "psx_step_state_init", "psx_step_state_advance", "psx_step_state_read",
+    "psx_step_state_init", "psx_step_state_advance", "psx_step_state_read", "psx_chunk_adam_step_unpack",
 ]
 
 
@@ -106,6 +106,7 @@ def lib():
         "psx_overflow_read": [vp, vp, sz, vp, vp],
         "psx_chunk_adam_step": [vp, vp, sz, C.POINTER(psx_adam_hyper), u32, vp],
         "psx_chunk_adam_step_noalloc": [vp, sz, C.POINTER(psx_adam_hyper), u32, vp, vp],
+        "psx_chunk_adam_step_unpack": [vp, vp, sz, C.POINTER(psx_adam_hyper), u32, vp, vp, sz, u64, vp],
         "psx_adam_step_scalars": [C.POINTER(psx_adam_hyper), vp],
         "psx_step_state_init": [vp, C.POINTER(psx_adam_hyper), C.POINTER(psx_scaler), vp],
         "psx_step_state_advance": [vp, vp],
@@ -244,6 +245,13 @@ def make_chunks(specs):
 def psx_chunk_adam_step(ctx, chunks, hyper, flags=0, stream=None, n_chunks=None):
     n = len(chunks) if n_chunks is None else n_chunks
     _ok(lib().psx_chunk_adam_step(ctx, chunks, n, C.byref(hyper), flags, _stream(stream)))
+
+
+def psx_chunk_adam_step_unpack(ctx, chunks, hyper, flags, p16_tensors, slots, chunk_elems, stream=None, n_chunks=None, n=None):
+    nc = len(chunks) if n_chunks is None else n_chunks
+    n = len(p16_tensors) if n is None else n
+    t = p16_tensors if isinstance(p16_tensors, C.Array) else ptr_array(p16_tensors)
+    _ok(lib().psx_chunk_adam_step_unpack(ctx, chunks, nc, C.byref(hyper), flags, t, slots, n, chunk_elems, _stream(stream)))
 
 
 def psx_chunk_adam_step_noalloc(chunks, hyper, flags=0, flag_out_dev=None, stream=None, n_chunks=None):

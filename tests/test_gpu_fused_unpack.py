@@ -1,0 +1,269 @@
+"""psx_chunk_adam_step_unpack: the Adam step that also writes the fp16 parameters into the tensors' own
+memory.  Compared with the oracle (its step, then its unpack of the param fp16 chunks) bit for bit: chunk
+lists, tensors, and the memory around the tensors, which must stay untouched."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2108_05818_amd import psx
+from paper_2108_05818_amd import workloads as W
+
+from gpu_util import DEV, SENT16, ChunkLists, bits16, f32
+
+pytestmark = pytest.mark.gpu
+
+
+def fill(cl, seed, loss_scale):
+    for k in range(cl.n):
+        u = cl.used[k]
+        if u:
+            cl.set("p32", k, W.params_np(u, seed + 10 * k))
+            cl.set("m", k, W.params_np(u, seed + 10 * k + 1) * np.float32(0.05))
+            cl.set("v", k, np.abs(W.params_np(u, seed + 10 * k + 2)) * np.float32(1e-4))
+            cl.set("g16", k, W.grads_f16_np(u, seed + 10 * k + 3, loss_scale))
+
+
+class Tensors:
+    """fp16 output tensors carved out of one device buffer full of sentinels: tensor i starts `gaps[i]`
+    elements after the end of the one before, so that destinations of every 2-byte alignment occur and any
+    element written outside a tensor shows."""
+
+    def __init__(self, numel, gaps):
+        self.numel = list(numel)
+        self.starts = []
+        pos = 0
+        for s, g in zip(numel, gaps):
+            pos += g
+            self.starts.append(pos)
+            pos += s
+        self.total = pos + 64
+        self.buf = torch.from_numpy(np.full(self.total, SENT16, np.uint16).view(np.int16)).to(DEV).view(torch.float16)
+        self.ptrs = [self.buf.data_ptr() + 2 * st for st in self.starts]
+
+    def bits(self):
+        return bits16(self.buf)
+
+    def expect(self, orc, slots, p16_chunks, C, only=None):
+        """The buffer as it must look: sentinels, with the oracle's unpack of the chunks in the tensors."""
+        want = np.full(self.total, SENT16, np.uint16)
+        outs = [np.zeros(s, np.uint16) for s in self.numel]
+        orc.unpack(outs, slots, p16_chunks, C)
+        for i, (st, s) in enumerate(zip(self.starts, self.numel)):
+            if only is None or i in only:
+                want[st:st + s] = outs[i]
+        return want
+
+
+def layout(orc, numel, C):
+    slots, used = psx.psx_chunk_layout(numel, C)
+    o_slots, o_used = orc.chunk_layout(numel, C)
+    assert used == [int(u) for u in o_used]
+    return slots, o_slots, used
+
+
+CASES = [
+    # tensor sizes, chunk elements: tensors that end inside tiles, single elements, a tensor larger than a chunk,
+    # one that fills a chunk exactly
+    ([1, 4000, 7, 9001, 333, 1, 2049, 4104, 15, 640], 4104),
+    # tensors aligned to tiles (the whole-tile store) next to ragged ones
+    ([2048, 1024, 256, 255, 257, 4096, 3, 8192], 8192),
+    # one chunk
+    ([70000, 12345, 3], 1 << 17),
+]
+
+
+@pytest.mark.parametrize("case", range(len(CASES)))
+@pytest.mark.parametrize("gap", [0, 1, 3])
+def test_fused_unpack_matches_oracle_step_and_unpack(orc, case, gap):
+    numel, C = CASES[case]
+    slots, o_slots, used = layout(orc, numel, C)
+    cl = ChunkLists(used, C)
+    fill(cl, 6100 + case, 1024.0)
+    tens = Tensors(numel, [gap + (i % 2) * (gap != 0) for i in range(len(numel))])
+    ctx = psx.psx_ctx_create(max_chunks=cl.n, max_tensors=len(numel))
+    try:
+        chunks = psx.make_chunks(cl.specs())
+        for step, (wd, adamw) in enumerate([(0.01, 0), (0.1, 1), (0.0, 0)], start=1):
+            hp = dict(lr=1e-3, weight_decay=wd, adamw_mode=adamw, step=step, loss_scale=1024.0)
+            psx.psx_chunk_adam_step_unpack(ctx, chunks, psx.make_hyper(**hp), psx.PSX_STEP_CHECK_FIRST, tens.ptrs, slots, C)
+            torch.cuda.synchronize()
+            assert cl.oracle_step(orc, orc.hyper(**hp)) == 0
+            assert cl.compare(f"step {step}") == 0.0
+            assert np.array_equal(tens.bits(), tens.expect(orc, o_slots, cl.np["p16"], C)), f"tensors after step {step}"
+    finally:
+        torch.cuda.synchronize()
+        psx.psx_ctx_destroy(ctx)
+
+
+def test_fused_unpack_equals_step_then_unpack(orc):
+    """Against the two-call form on a copy of the same state: chunk lists and tensors bit for bit."""
+    numel, C = CASES[0]
+    slots, o_slots, used = layout(orc, numel, C)
+    a, b = ChunkLists(used, C), ChunkLists(used, C)
+    fill(a, 6200, 512.0)
+    fill(b, 6200, 512.0)
+    ta, tb = Tensors(numel, [1] * len(numel)), Tensors(numel, [1] * len(numel))
+    ctx = psx.psx_ctx_create(max_chunks=a.n, max_tensors=len(numel))
+    try:
+        hp = psx.make_hyper(lr=1e-3, weight_decay=0.01, step=3, loss_scale=512.0)
+        psx.psx_chunk_adam_step_unpack(ctx, psx.make_chunks(a.specs()), hp, psx.PSX_STEP_CHECK_FIRST, ta.ptrs, slots, C)
+        psx.psx_chunk_adam_step(ctx, psx.make_chunks(b.specs()), hp, psx.PSX_STEP_CHECK_FIRST)
+        psx.psx_unpack(ctx, psx.PSX_F16, tb.ptrs, slots, b.p16, C)
+        torch.cuda.synchronize()
+        assert np.array_equal(ta.bits(), tb.bits())
+        for k in range(a.n):
+            for name in ("p32", "m", "v"):
+                assert f32(getattr(a, name)[k]).tobytes() == f32(getattr(b, name)[k]).tobytes(), (k, name)
+            assert np.array_equal(bits16(a.p16[k]), bits16(b.p16[k])), k
+    finally:
+        torch.cuda.synchronize()
+        psx.psx_ctx_destroy(ctx)
+
+
+def test_skipped_step_writes_no_tensor_and_partial_lists_leave_the_rest_alone(orc):
+    numel, C = CASES[0]
+    slots, o_slots, used = layout(orc, numel, C)
+    cl = ChunkLists(used, C)
+    fill(cl, 6300, 1024.0)
+    tens = Tensors(numel, [2] * len(numel))
+    ctx = psx.psx_ctx_create(max_chunks=cl.n, max_tensors=len(numel))
+    try:
+        chunks = psx.make_chunks(cl.specs())
+        # an inf in the last used element of the last chunk: the step is skipped, tensors keep their sentinels
+        k = max(i for i in range(cl.n) if used[i])
+        keep = cl.np["g16"][k][used[k] - 1]
+        cl.set("g16", k, np.array([0x7C00], np.uint16), at=used[k] - 1)
+        hp = dict(lr=1e-3, weight_decay=0.01, step=1, loss_scale=1024.0)
+        psx.psx_chunk_adam_step_unpack(ctx, chunks, psx.make_hyper(**hp), psx.PSX_STEP_CHECK_FIRST, tens.ptrs, slots, C)
+        flag, _ = psx.psx_overflow_read(ctx)
+        assert flag == 1 and cl.oracle_step(orc, orc.hyper(**hp)) == 1
+        assert cl.compare("skipped") == 0.0
+        assert (tens.bits() == SENT16).all()
+        # the same call with every second tensor only: the others, and everything between, stay as they are
+        cl.set("g16", k, np.array([keep], np.uint16), at=used[k] - 1)
+        only = [i for i in range(len(numel)) if i % 2 == 0]
+        part_slots = (psx.psx_slot * len(only))(*[slots[i] for i in only])
+        psx.psx_chunk_adam_step_unpack(ctx, chunks, psx.make_hyper(**hp), psx.PSX_STEP_CHECK_FIRST,
+                                       [tens.ptrs[i] for i in only], part_slots, C)
+        torch.cuda.synchronize()
+        assert cl.oracle_step(orc, orc.hyper(**hp)) == 0
+        assert cl.compare("partial") == 0.0
+        assert np.array_equal(tens.bits(), tens.expect(orc, o_slots, cl.np["p16"], C, only=set(only)))
+    finally:
+        torch.cuda.synchronize()
+        psx.psx_ctx_destroy(ctx)
+
+
+def test_fused_unpack_refuses_what_it_cannot_do(orc):
+    numel, C = [5000, 3000, 100], 4096
+    slots, o_slots, used = layout(orc, numel, C)
+    cl = ChunkLists(used, C)
+    fill(cl, 6400, 1024.0)
+    tens = Tensors(numel, [0] * len(numel))
+    ctx = psx.psx_ctx_create(max_chunks=cl.n, max_tensors=len(numel))
+    host = [psx.PinnedF32(C, fill=0.0) for _ in range(3)]
+    try:
+        hp = psx.make_hyper(lr=1e-3, step=1, loss_scale=1024.0)
+        before = [bits16(cl.p16[k]).copy() for k in range(cl.n)]
+        # two slots that overlap
+        bad = (psx.psx_slot * 3)(*[slots[i] for i in range(3)])
+        bad[1].offset = slots[1].offset - 1
+        with pytest.raises(psx.PsxError, match="overlap"):
+            psx.psx_chunk_adam_step_unpack(ctx, psx.make_chunks(cl.specs()), hp, 0, tens.ptrs, bad, C)
+        # a slot that runs past the chunk list
+        bad = (psx.psx_slot * 3)(*[slots[i] for i in range(3)])
+        bad[2].numel = cl.n * C
+        with pytest.raises(psx.PsxError, match="runs past"):
+            psx.psx_chunk_adam_step_unpack(ctx, psx.make_chunks(cl.specs()), hp, 0, tens.ptrs, bad, C)
+        # a chunk with a host side
+        specs = cl.specs(loc=[(psx.PSX_LOC_HBM, psx.PSX_LOC_HBM)] * (cl.n - 1) + [(psx.PSX_LOC_HOST, psx.PSX_LOC_HOST)],
+                         host=[None] * (cl.n - 1) + [host])
+        with pytest.raises(psx.PsxError, match="stay in HBM"):
+            psx.psx_chunk_adam_step_unpack(ctx, psx.make_chunks(specs), hp, 0, tens.ptrs, slots, C)
+        # another launch shape
+        psx.psx_ctx_set_tuning(ctx, psx.PSX_TUNE_ADAM_THREADS, 256)
+        with pytest.raises(psx.PsxError, match="default launch shape"):
+            psx.psx_chunk_adam_step_unpack(ctx, psx.make_chunks(cl.specs()), hp, 0, tens.ptrs, slots, C)
+        psx.psx_ctx_set_tuning(ctx, psx.PSX_TUNE_ADAM_THREADS, 64)
+        torch.cuda.synchronize()
+        assert (tens.bits() == SENT16).all()
+        for k in range(cl.n):
+            assert np.array_equal(bits16(cl.p16[k]), before[k])
+    finally:
+        torch.cuda.synchronize()
+        psx.psx_ctx_destroy(ctx)
+        for b in host:
+            b.free()
+
+
+def test_fused_step_recorded_into_a_graph_and_replayed(orc):
+    """Gradient pack with the overflow test, the fused update + unpack from the device-resident step state and
+    the bookkeeping, recorded once and replayed as training steps (one of them with an inf), each replay
+    compared with the free-running oracle."""
+    from gpu_util import from_bits16
+    w = W.config1_tiny()
+    hp = dict(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01, adamw_mode=0)
+    slots, used = psx.psx_chunk_layout(w.numel, w.chunk_elems)
+    o_slots, _ = orc.chunk_layout(w.numel, w.chunk_elems)
+    Cn, nch = w.chunk_elems, len(used)
+    ctx = psx.psx_ctx_create(max_chunks=nch, max_tensors=len(w.numel))
+    try:
+        cl = ChunkLists(used, Cn)
+        for k in range(nch):
+            cl.set("p32", k, W.params_np(used[k], 6500 + k))
+            cl.set("m", k, np.zeros(used[k], np.float32))
+            cl.set("v", k, np.zeros(used[k], np.float32))
+        o_scaler = orc.scaler(1024.0, 2)
+        hyper = psx.make_hyper(**hp)
+        psx.psx_step_state_init(ctx, hyper, psx.make_scaler(1024.0, 2))
+        chunks = psx.make_chunks(cl.specs())
+        g_t = [torch.zeros(s, dtype=torch.float16, device=DEV) for s in w.numel]
+        tens = Tensors(w.numel, [1] * len(w.numel))
+        g_ptrs, o_ptrs = psx.ptr_array(g_t), psx.ptr_array(tens.ptrs)
+        want = np.full(tens.total, SENT16, np.uint16)
+
+        def one_step():
+            psx.psx_overflow_reset(ctx)
+            psx.psx_pack(ctx, psx.PSX_F16, g_ptrs, slots, cl.g16, Cn, flags=psx.PSX_PACK_CHECK_OVERFLOW, n=len(g_t))
+            psx.psx_chunk_adam_step_unpack(ctx, chunks, hyper, psx.PSX_STEP_USE_FLAG | psx.PSX_STEP_DEVICE_STATE, o_ptrs, slots, Cn,
+                                           n=len(g_t))
+            psx.psx_step_state_advance(ctx)
+
+        def new_gradients(it, plant):
+            g_np = [W.grads_f16_np(s, 6600 + 100 * it + i, o_scaler.scale) for i, s in enumerate(w.numel)]
+            if plant:
+                g_np[5][3] = 0x7C00
+            for t, a in zip(g_t, g_np):
+                t.copy_(from_bits16(a))
+            return g_np
+
+        def oracle_follows(g_np, tag):
+            nonlocal want
+            orc.pack(g_np, o_slots, cl.np["g16"], Cn)
+            flag = cl.oracle_step(orc, orc.hyper(step=o_scaler.step, loss_scale=o_scaler.scale, **hp))
+            orc.scaler_update(o_scaler, flag)
+            torch.cuda.synchronize()
+            assert cl.compare(tag) == 0.0
+            if not flag:                                  # a skipped step writes no tensor
+                want = tens.expect(orc, o_slots, cl.np["p16"], Cn)
+            assert np.array_equal(tens.bits(), want), tag
+            s, last_flag, _ = psx.psx_step_state_read(ctx)
+            assert (float(s.scale), int(s.step)) == (float(o_scaler.scale), int(o_scaler.step)) and last_flag == flag
+            return flag
+
+        g_np = new_gradients(0, False)
+        one_step()
+        oracle_follows(g_np, "eager step")
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            one_step()
+        flags = []
+        for it in range(1, 6):
+            g_np = new_gradients(it, plant=(it == 3))
+            graph.replay()
+            flags.append(oracle_follows(g_np, f"replay {it}"))
+            _ = torch.ones(1000, device=DEV).sum().item()          # eager work between replays
+        assert flags == [0, 0, 1, 0, 0]
+    finally:
+        torch.cuda.synchronize()
+        psx.psx_ctx_destroy(ctx)
