@@ -74,10 +74,11 @@ CASES = [
 
 @pytest.mark.parametrize("case", range(len(CASES)))
 @pytest.mark.parametrize("gap", [0, 1, 3])
-def test_fused_unpack_matches_oracle_step_and_unpack(orc, case, gap):
+@pytest.mark.parametrize("alias", [False, True])
+def test_fused_unpack_matches_oracle_step_and_unpack(orc, case, gap, alias):
     numel, C = CASES[case]
     slots, o_slots, used = layout(orc, numel, C)
-    cl = ChunkLists(used, C)
+    cl = ChunkLists(used, C, alias=alias)               # alias: the gradients sit in the fp16 parameter chunks
     fill(cl, 6100 + case, 1024.0)
     tens = Tensors(numel, [gap + (i % 2) * (gap != 0) for i in range(len(numel))])
     ctx = psx.psx_ctx_create(max_chunks=cl.n, max_tensors=len(numel))
@@ -85,6 +86,9 @@ def test_fused_unpack_matches_oracle_step_and_unpack(orc, case, gap):
         chunks = psx.make_chunks(cl.specs())
         for step, (wd, adamw) in enumerate([(0.01, 0), (0.1, 1), (0.0, 0)], start=1):
             hp = dict(lr=1e-3, weight_decay=wd, adamw_mode=adamw, step=step, loss_scale=1024.0)
+            for k in range(cl.n):                       # fresh gradients (with chunk reuse the last step overwrote them)
+                if used[k]:
+                    cl.set("g16", k, W.grads_f16_np(used[k], 6150 + 100 * step + k, 1024.0))
             psx.psx_chunk_adam_step_unpack(ctx, chunks, psx.make_hyper(**hp), psx.PSX_STEP_CHECK_FIRST, tens.ptrs, slots, C)
             torch.cuda.synchronize()
             assert cl.oracle_step(orc, orc.hyper(**hp)) == 0
