@@ -237,8 +237,9 @@ def test_config2_gpt1b_full_size_every_chunk(orc, reuse):
         assert (st.scaler.scale, st.scaler.step) == (o_scaler.scale, o_scaler.step) == (w.loss_scale / 2, 3)
         st.g_t[victim][777] = saved
         del every
-        # one more step at the halved scale: the state after three updates, every chunk again
-        flag = bench.run_step(st, fused_check=True)
+        # one more step at the halved scale, this one with the fp16 unpack inside the Adam launch
+        # (psx_chunk_adam_step_unpack): the state after three updates and the tensors it wrote, every chunk again
+        flag = bench.run_step(st, fused_check=True, fused_unpack=True)
         torch.cuda.synchronize()
         assert flag == 0
         hypers.append(hyper_of(orc, w, o_scaler.step, o_scaler.scale))
