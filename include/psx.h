@@ -278,10 +278,14 @@ int32_t psx_adam_step_scalars(const psx_adam_hyper *hyper, float *out);
  *                           elements of the chunk list that no slot covers are written to the chunk only.
  * Every chunk with used > 0 must stay in HBM (loc_in == loc_out == PSX_LOC_HBM, PSX_EXEC_GPU) and the Adam
  * launch shape must be the default one, else PSX_EINVAL.  Elements of a slot behind its chunk's `used`
- * are not written.  On a skipped step (overflow flag set) no tensor is written: they keep the parameters
- * of the last applied step, which are the ones the chunk list holds.  Flags, errors, streams and graph
- * capture as for psx_chunk_adam_step; results are bit-identical to psx_chunk_adam_step followed by
- * psx_unpack(PSX_F16) of the p16 chunks.
+ * are not written.  The fused store pays when the tensors' memory is aligned like their slots (the usual
+ * case: 64-element multiples at 128-byte aligned addresses); where most of it is not, pieces of a tile
+ * end inside 128-byte lines of the tensors and the two-launch form is faster, so the library then runs
+ * the update and the unpack as two launches of its own (PSX_TUNE_FUSED_UNPACK overrides the choice).
+ * On a skipped step (overflow flag set) the fused form writes no tensor and the two-launch form rewrites
+ * them with the unchanged chunk content: either way they hold the chunk list's parameters if they did
+ * before.  Flags, errors, streams and graph capture as for psx_chunk_adam_step; results are bit-identical
+ * to psx_chunk_adam_step followed by psx_unpack(PSX_F16) of the p16 chunks.
  */
 int32_t psx_chunk_adam_step_unpack(psx_ctx *ctx, const psx_chunk *chunks, size_t n_chunks,
                                    const psx_adam_hyper *hyper, uint32_t flags,
@@ -378,6 +382,7 @@ int32_t psx_step_state_read(psx_ctx *ctx, psx_scaler *scaler, uint32_t *last_fla
 #define PSX_TUNE_CPU_TILE_ELEMS     12u  /* elements per tile of the PSX_EXEC_CPU pipeline (multiple of 16)  */
 #define PSX_TUNE_CPU_ISA            13u  /* PSX_EXEC_CPU vectors: 0 = widest the host has (AVX-512, else AVX2), 1 = AVX2 */
 #define PSX_TUNE_COPY_THREADS       14u
+#define PSX_TUNE_FUSED_UNPACK       15u  /* psx_chunk_adam_step_unpack: 0 = the library decides (default), 1 = always write the tensors from the Adam launch, 2 = always update, then unpack */
 int32_t psx_ctx_set_tuning(psx_ctx *ctx, uint32_t key, int64_t value);
 
 /* Kernel timing with HIP events on the caller's stream (off by default). */

@@ -97,6 +97,7 @@ struct Tuning {
     int cpu_threads = 0;           // PSX_EXEC_CPU: worker threads (0: min(hardware threads, 16))
     uint64_t cpu_tile_elems = 4u << 20;   // PSX_EXEC_CPU: elements per pipeline tile
     int cpu_isa = 0;               // PSX_EXEC_CPU: 0 widest vectors the host has (AVX-512 or AVX2), 1 AVX2
+    int fused_unpack = 0;          // psx_chunk_adam_step_unpack: 0 by the alignment of the slots, 1 always inside the launch, 2 never
 };
 
 // Elements per tile of the Adam kernel (threads x 4 elements x unroll).

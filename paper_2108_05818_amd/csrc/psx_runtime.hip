@@ -395,6 +395,10 @@ extern "C" int32_t psx_ctx_set_tuning(psx_ctx *c, uint32_t key, int64_t value) {
             if (value != 64 && value != 256) return fail(PSX_EINVAL, "copy threads must be 64 or 256");
             c->tune.copy_threads = (int)value;
             break;
+        case PSX_TUNE_FUSED_UNPACK:
+            if (value < 0 || value > 2) return fail(PSX_EINVAL, "fused unpack must be 0 (by alignment), 1 (always) or 2 (never)");
+            c->tune.fused_unpack = (int)value;
+            break;
         case PSX_TUNE_HOST_MODE:
             if (value != 0 && value != 1) return fail(PSX_EINVAL, "host mode must be 0 (staged copies) or 1 (direct access)");
             c->tune.host_mode = (int)value;
@@ -1199,10 +1203,40 @@ int32_t adam_step_impl(psx_ctx *c, const psx_chunk *chunks, size_t n_chunks, con
     if (!c->moves.empty() && (rc = upload_described(c->move_tbl, c->moves, c->blob, s, &mtbl, &mtbl_begins)) != PSX_OK) return rc;
     auto view = [&](size_t off, size_t n) { return RunView{tbl + off, tbl_begins + off, (uint32_t)n}; };
     const uint32_t *flag = use_flag ? c->flags_dev : nullptr;
+    // the fp16 tensors: written from inside the resident launch, or by an unpack launch behind it when most of
+    // their memory is not aligned like their slots (tile pieces would end inside the tensors' 128-byte lines)
     OutView out_view{nullptr, nullptr};
+    bool fuse_out = false;
+    SegView unpack_view{nullptr, nullptr, 0, nullptr, 0};
+    uint64_t unpack_tiles = 0;
     if (out != nullptr) {
         if ((rc = build_out(c, chunks, n_chunks, *out, pl.n_res)) != PSX_OK) return rc;
-        if ((rc = upload_out(c, s, &out_view)) != PSX_OK) return rc;
+        uint64_t aligned = 0, covered = 0;
+        for (const OutSeg &g : c->outs) {
+            covered += g.n;
+            if ((reinterpret_cast<uintptr_t>(g.dst) - 2 * g.off) % 128 == 0) aligned += g.n;
+        }
+        fuse_out = c->tune.fused_unpack == 1 || (c->tune.fused_unpack == 0 && 2 * aligned >= covered);
+        if (fuse_out) {
+            if ((rc = upload_out(c, s, &out_view)) != PSX_OK) return rc;
+        } else {
+            c->copy_unroll_now = copy_unroll_for(c->tune, c->outs.size());
+            const uint64_t tile_elems = copy_tile_bytes(c->tune, c->copy_unroll_now) / 2;
+            c->segs.clear();
+            for (const OutSeg &g : c->outs) {
+                CopySeg q;
+                q.src = static_cast<const unsigned char *>(chunks[g.pad].p16) + g.off * 2;
+                q.dst = reinterpret_cast<unsigned char *>(g.dst);
+                q.n = g.n; q.tile_begin = unpack_tiles; q.chunk = (uint32_t)g.pad; q.pad = 0;
+                c->segs.push_back(q);
+                unpack_tiles += copy_tiles_of(q.dst, q.n, 2, tile_elems);
+            }
+            if (unpack_tiles != 0 &&
+                (rc = upload_segments(c->unpack_tbl, c->segs, unpack_tiles, c->blob, s, &unpack_view.segs, &unpack_view.begins,
+                                      &unpack_view.hints, &unpack_view.shift)) != PSX_OK)
+                return rc;
+            unpack_view.n = (uint32_t)c->segs.size();
+        }
     }
 
     // ---- overflow check over every gradient chunk
@@ -1241,11 +1275,18 @@ int32_t adam_step_impl(psx_ctx *c, const psx_chunk *chunks, size_t n_chunks, con
         c->t_adam.valid = false;
         if (pl.res_tiles != 0) {
             if ((rc = span_begin(c, c->t_adam, s)) != PSX_OK) return rc;
-            if (out != nullptr) PSX_HIP(launch_adam_out(view(0, pl.n_res), pl.res_tiles, sc, flag, c->tune, c->n_cu, s, sc_dev, out_view));
+            if (fuse_out) PSX_HIP(launch_adam_out(view(0, pl.n_res), pl.res_tiles, sc, flag, c->tune, c->n_cu, s, sc_dev, out_view));
             else PSX_HIP(launch_adam(view(0, pl.n_res), pl.res_tiles, sc, flag, c->tune, c->n_cu, s, sc_dev));
             if ((rc = span_end(c, c->t_adam, s)) != PSX_OK) return rc;
             if (pl.n_recast != 0)
                 PSX_HIP(launch_recast_if_flag(view(pl.n_res, pl.n_recast), pl.recast_tiles, flag, c->tune, c->n_cu, s));
+            if (out != nullptr && !fuse_out && unpack_tiles != 0) {
+                if ((rc = span_begin(c, c->t_unpack, s)) != PSX_OK) return rc;
+                Tuning tn = c->tune;
+                tn.copy_unroll = c->copy_unroll_now;
+                PSX_HIP(launch_copy(unpack_view, unpack_tiles, 2u, nullptr, nullptr, tn, c->n_cu, s));
+                if ((rc = span_end(c, c->t_unpack, s)) != PSX_OK) return rc;
+            }
         }
 
         // ---- host-resident chunks, direct mode: one persistent launch on the side stream, concurrent with

@@ -24,6 +24,7 @@ PSX_TUNE_ADAM_THREADS, PSX_TUNE_ADAM_WG_PER_CU, PSX_TUNE_COPY_UNROLL = 5, 6, 7
 PSX_TUNE_HOST_MODE, PSX_TUNE_HOST_GRID, PSX_TUNE_HOST_UNROLL = 8, 9, 10
 PSX_TUNE_CPU_THREADS, PSX_TUNE_CPU_TILE_ELEMS, PSX_TUNE_CPU_ISA = 11, 12, 13
 PSX_TUNE_COPY_THREADS = 14
+PSX_TUNE_FUSED_UNPACK = 15
 PSX_NOALLOC_MAX_CHUNKS, PSX_NOALLOC_SCRATCH_BYTES = 1024, 262144
 
 EXPORTS = [

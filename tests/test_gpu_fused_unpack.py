@@ -75,7 +75,10 @@ CASES = [
 @pytest.mark.parametrize("case", range(len(CASES)))
 @pytest.mark.parametrize("gap", [0, 1, 3])
 @pytest.mark.parametrize("alias", [False, True])
-def test_fused_unpack_matches_oracle_step_and_unpack(orc, case, gap, alias):
+@pytest.mark.parametrize("mode", [0, 1, 2])
+def test_fused_unpack_matches_oracle_step_and_unpack(orc, case, gap, alias, mode):
+    """mode: PSX_TUNE_FUSED_UNPACK (0 the library's choice by alignment, 1 always inside the Adam launch, 2 always
+    as an unpack launch behind it): the same bits every way."""
     numel, C = CASES[case]
     slots, o_slots, used = layout(orc, numel, C)
     cl = ChunkLists(used, C, alias=alias)               # alias: the gradients sit in the fp16 parameter chunks
@@ -83,6 +86,7 @@ def test_fused_unpack_matches_oracle_step_and_unpack(orc, case, gap, alias):
     tens = Tensors(numel, [gap + (i % 2) * (gap != 0) for i in range(len(numel))])
     ctx = psx.psx_ctx_create(max_chunks=cl.n, max_tensors=len(numel))
     try:
+        psx.psx_ctx_set_tuning(ctx, psx.PSX_TUNE_FUSED_UNPACK, mode)
         chunks = psx.make_chunks(cl.specs())
         for step, (wd, adamw) in enumerate([(0.01, 0), (0.1, 1), (0.0, 0)], start=1):
             hp = dict(lr=1e-3, weight_decay=wd, adamw_mode=adamw, step=step, loss_scale=1024.0)
@@ -132,6 +136,7 @@ def test_skipped_step_writes_no_tensor_and_partial_lists_leave_the_rest_alone(or
     tens = Tensors(numel, [2] * len(numel))
     ctx = psx.psx_ctx_create(max_chunks=cl.n, max_tensors=len(numel))
     try:
+        psx.psx_ctx_set_tuning(ctx, psx.PSX_TUNE_FUSED_UNPACK, 1)      # inside the launch: a skipped step must write nothing
         chunks = psx.make_chunks(cl.specs())
         # an inf in the last used element of the last chunk: the step is skipped, tensors keep their sentinels
         k = max(i for i in range(cl.n) if used[i])
@@ -200,7 +205,8 @@ def test_fused_unpack_refuses_what_it_cannot_do(orc):
             b.free()
 
 
-def test_fused_step_recorded_into_a_graph_and_replayed(orc):
+@pytest.mark.parametrize("mode", [1, 2])
+def test_fused_step_recorded_into_a_graph_and_replayed(orc, mode):
     """Gradient pack with the overflow test, the fused update + unpack from the device-resident step state and
     the bookkeeping, recorded once and replayed as training steps (one of them with an inf), each replay
     compared with the free-running oracle."""
@@ -220,6 +226,7 @@ def test_fused_step_recorded_into_a_graph_and_replayed(orc):
         o_scaler = orc.scaler(1024.0, 2)
         hyper = psx.make_hyper(**hp)
         psx.psx_step_state_init(ctx, hyper, psx.make_scaler(1024.0, 2))
+        psx.psx_ctx_set_tuning(ctx, psx.PSX_TUNE_FUSED_UNPACK, mode)
         chunks = psx.make_chunks(cl.specs())
         g_t = [torch.zeros(s, dtype=torch.float16, device=DEV) for s in w.numel]
         tens = Tensors(w.numel, [1] * len(w.numel))
