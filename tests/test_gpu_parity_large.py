@@ -271,6 +271,8 @@ def test_config3_ragged_full_size_every_chunk(orc):
             # gradients are generated once at set-up; what changes from step to step is the unscale value.
             # The last two steps write the fp16 tensors from inside the Adam launch (tiles that span tensors,
             # tensors off the 8-byte grid of their tiles: the 5000 slots have every alignment)
+            # (step 3 inside the launch whatever the alignment, step 4 the library's choice: an unpack launch of its own)
+            psx.psx_ctx_set_tuning(st.ctx, psx.PSX_TUNE_FUSED_UNPACK, 1 if step == 3 else 0)
             flag = bench.run_step(st, fused_check=step % 2 == 0, fused_unpack=step >= 3)
             torch.cuda.synchronize()
             if saved is not None:
