@@ -340,12 +340,16 @@ int32_t psx_loss_scale_update(psx_scaler *s, uint32_t overflow);
  *                           rules of psx_loss_scale_update (overflow: scale halved with floor 1, good_steps
  *                           cleared, t unchanged; else t and good_steps advance, growth_interval good steps
  *                           double the scale), then derives the scalars of the next update.  One tiny
- *                           launch on `stream`; asynchronous.
+ *                           launch on `stream`; asynchronous.  With PSX_ADVANCE_CLEAR_FLAGS it also clears
+ *                           the context's overflow flags (global and per chunk) once it has read them, so
+ *                           the next step needs no psx_overflow_reset: one launch less per step, which is
+ *                           what a small model's step consists of.
  *   psx_step_state_read     copies the state back (synchronises `stream`): scaler, the flag of the step
  *                           closed last, the number of steps skipped so far; each may be NULL.
  * psx_chunk_adam_step(PSX_STEP_DEVICE_STATE) updates with the state's t and loss scale. */
 int32_t psx_step_state_init(psx_ctx *ctx, const psx_adam_hyper *hyper, const psx_scaler *scaler, void *stream);
-int32_t psx_step_state_advance(psx_ctx *ctx, void *stream);
+#define PSX_ADVANCE_CLEAR_FLAGS 1u
+int32_t psx_step_state_advance(psx_ctx *ctx, uint32_t flags, void *stream);
 int32_t psx_step_state_read(psx_ctx *ctx, psx_scaler *scaler, uint32_t *last_flag, uint64_t *skipped, void *stream);
 
 /* ------------------------------------------------------------------ tuning and timing

@@ -182,9 +182,9 @@ hipError_t launch_adam_move(const MoveView &mv, uint64_t n_tiles, const AdamScal
                             const uint32_t *flag_dev, const Tuning &t, uint32_t grid, hipStream_t s,
                             const AdamScalars *sc_dev = nullptr);
 // Device-resident step state: write `init` and derive its scalars; close a step (loss-scale bookkeeping from
-// *flag_dev, then the scalars of the next update).  One thread each.
+// flags_dev[0], then the scalars of the next update; n_clear != 0: the first n_clear flags are cleared once read).
 hipError_t launch_step_state_init(StepState *st, const StepState &init, hipStream_t s);
-hipError_t launch_step_state_advance(StepState *st, const uint32_t *flag_dev, hipStream_t s);
+hipError_t launch_step_state_advance(StepState *st, uint32_t *flags_dev, uint64_t n_clear, hipStream_t s);
 // skipped step with p16 aliasing g16: p16 = fp16(p32), only when *flag_dev != 0
 hipError_t launch_recast_if_flag(const RunView &rv, uint64_t n_tiles,
                                  const uint32_t *flag_dev, const Tuning &t, int n_cu, hipStream_t s);

@@ -796,9 +796,14 @@ __global__ void step_state_init_kernel(StepState *st, StepState init) {
     derive_scalars(st);
 }
 
-__global__ void step_state_advance_kernel(StepState *st, const uint32_t *__restrict__ flag) {
-    if (blockIdx.x != 0 || threadIdx.x != 0) return;
-    const uint32_t overflow = *flag != 0 ? 1u : 0u;
+// One workgroup.  Every thread reads the global flag before any of them clears it; thread 0 does the
+// bookkeeping; then, if asked to, all of them clear the n_clear flags (global + per chunk) for the next step.
+__global__ void step_state_advance_kernel(StepState *st, uint32_t *flags, uint64_t n_clear) {
+    if (blockIdx.x != 0) return;
+    const uint32_t overflow = flags[0] != 0 ? 1u : 0u;
+    __syncthreads();
+    for (uint64_t i = threadIdx.x; i < n_clear; i += blockDim.x) flags[i] = 0u;
+    if (threadIdx.x != 0) return;
     if (overflow) {
         const float half = st->scale * 0.5f;
         st->scale = half < 1.0f ? 1.0f : half;
@@ -823,8 +828,8 @@ hipError_t launch_step_state_init(StepState *st, const StepState &init, hipStrea
     return hipGetLastError();
 }
 
-hipError_t launch_step_state_advance(StepState *st, const uint32_t *flag_dev, hipStream_t s) {
-    hipLaunchKernelGGL(step_state_advance_kernel, dim3(1), dim3(64), 0, s, st, flag_dev);
+hipError_t launch_step_state_advance(StepState *st, uint32_t *flags_dev, uint64_t n_clear, hipStream_t s) {
+    hipLaunchKernelGGL(step_state_advance_kernel, dim3(1), dim3(64), 0, s, st, flags_dev, n_clear);
     return hipGetLastError();
 }
 

@@ -727,12 +727,14 @@ extern "C" int32_t psx_step_state_init(psx_ctx *c, const psx_adam_hyper *hyper, 
     return PSX_OK;
 }
 
-extern "C" int32_t psx_step_state_advance(psx_ctx *c, void *stream) {
+extern "C" int32_t psx_step_state_advance(psx_ctx *c, uint32_t flags, void *stream) {
     if (c == nullptr) return fail(PSX_EINVAL, "psx_step_state_advance: ctx is NULL");
+    if (flags & ~PSX_ADVANCE_CLEAR_FLAGS) return fail(PSX_EINVAL, "psx_step_state_advance: unknown flags 0x%x", flags);
     if (!c->state_on) return fail(PSX_EINVAL, "psx_step_state_advance: psx_step_state_init has not been called");
     int32_t rc = set_device_guard(c);
     if (rc != PSX_OK) return rc;
-    PSX_HIP(launch_step_state_advance(c->state_dev, c->flags_dev, static_cast<hipStream_t>(stream)));
+    PSX_HIP(launch_step_state_advance(c->state_dev, c->flags_dev, (flags & PSX_ADVANCE_CLEAR_FLAGS) ? c->flags_n : 0,
+                                      static_cast<hipStream_t>(stream)));
     return PSX_OK;
 }
 

@@ -25,6 +25,7 @@ PSX_TUNE_HOST_MODE, PSX_TUNE_HOST_GRID, PSX_TUNE_HOST_UNROLL = 8, 9, 10
 PSX_TUNE_CPU_THREADS, PSX_TUNE_CPU_TILE_ELEMS, PSX_TUNE_CPU_ISA = 11, 12, 13
 PSX_TUNE_COPY_THREADS = 14
 PSX_TUNE_FUSED_UNPACK = 15
+PSX_ADVANCE_CLEAR_FLAGS = 1
 PSX_NOALLOC_MAX_CHUNKS, PSX_NOALLOC_SCRATCH_BYTES = 1024, 262144
 
 EXPORTS = [
@@ -110,7 +111,7 @@ def lib():
         "psx_chunk_adam_step_unpack": [vp, vp, sz, C.POINTER(psx_adam_hyper), u32, vp, vp, sz, u64, vp],
         "psx_adam_step_scalars": [C.POINTER(psx_adam_hyper), vp],
         "psx_step_state_init": [vp, C.POINTER(psx_adam_hyper), C.POINTER(psx_scaler), vp],
-        "psx_step_state_advance": [vp, vp],
+        "psx_step_state_advance": [vp, u32, vp],
         "psx_step_state_read": [vp, C.POINTER(psx_scaler), C.POINTER(u32), C.POINTER(u64), vp],
         "psx_loss_scale_update": [C.POINTER(psx_scaler), u32],
         "psx_ctx_set_tuning": [vp, u32, C.c_int64],
@@ -274,8 +275,8 @@ def psx_step_state_init(ctx, hyper, scaler, stream=None):
     _ok(lib().psx_step_state_init(ctx, C.byref(hyper), C.byref(scaler), _stream(stream)))
 
 
-def psx_step_state_advance(ctx, stream=None):
-    _ok(lib().psx_step_state_advance(ctx, _stream(stream)))
+def psx_step_state_advance(ctx, flags=0, stream=None):
+    _ok(lib().psx_step_state_advance(ctx, flags, _stream(stream)))
 
 
 def psx_step_state_read(ctx, stream=None):

@@ -20,9 +20,11 @@ def scaler_tuple(s):
 
 
 @pytest.mark.parametrize("alias", [False, True])
-def test_device_step_state_follows_the_oracle_scaler(orc, alias):
+@pytest.mark.parametrize("clear", [False, True])
+def test_device_step_state_follows_the_oracle_scaler(orc, alias, clear):
     """40 steps over a ragged chunk list, overflows planted at chosen steps, growth interval 3: the update takes
-    t and the loss scale from the device, the bookkeeping runs on the device, nothing is read back inside a step."""
+    t and the loss scale from the device, the bookkeeping runs on the device, nothing is read back inside a step.
+    clear: the flags are cleared by the bookkeeping kernel (PSX_ADVANCE_CLEAR_FLAGS) instead of a reset per step."""
     w = W.config1_tiny()
     slots, used = psx.psx_chunk_layout(w.numel, w.chunk_elems)
     o_slots, _ = orc.chunk_layout(w.numel, w.chunk_elems)
@@ -47,10 +49,14 @@ def test_device_step_state_follows_the_oracle_scaler(orc, alias):
             if it in bad_steps:
                 i = int(rng.integers(0, len(w.numel)))
                 g_np[i][int(rng.integers(0, w.numel[i]))] = rng.choice(W.specials_f16())
-            psx.psx_overflow_reset(ctx)
+            if not clear or it == 0:
+                psx.psx_overflow_reset(ctx)
             psx.psx_pack(ctx, psx.PSX_F16, [from_bits16(a) for a in g_np], slots, cl.g16, Cn, flags=psx.PSX_PACK_CHECK_OVERFLOW)
             psx.psx_chunk_adam_step(ctx, chunks, hyper, psx.PSX_STEP_USE_FLAG | psx.PSX_STEP_DEVICE_STATE)
-            psx.psx_step_state_advance(ctx)
+            psx.psx_step_state_advance(ctx, psx.PSX_ADVANCE_CLEAR_FLAGS if clear else 0)
+            if clear:
+                flag_now, per_chunk = psx.psx_overflow_read(ctx, nch)
+                assert flag_now == 0 and not any(per_chunk)
             # the oracle, free-running, with its host scaler
             orc.pack(g_np, o_slots, cl.np["g16"], Cn)
             o_flag = cl.oracle_step(orc, orc.hyper(step=o_scaler.step, loss_scale=o_scaler.scale, **HP))
