@@ -32,8 +32,9 @@
  *     equal those of the previous call of its kind on the context uploads
  *     nothing and enqueues kernel launches only; in that state
  *     psx_overflow_reset, psx_pack, psx_unpack, psx_overflow_check without
- *     read-back, psx_chunk_adam_step over HBM-resident chunks with
- *     PSX_STEP_DEVICE_STATE, and psx_step_state_advance may be recorded into a
+ *     read-back, psx_chunk_adam_step and psx_chunk_adam_step_unpack over
+ *     HBM-resident chunks with PSX_STEP_DEVICE_STATE, and
+ *     psx_step_state_advance may be recorded into a
  *     graph (stream capture) and replayed: every replay is one more training
  *     step, with t and the loss scale advancing on the device.  Issue the same
  *     calls once outside the capture first.  A call that would have to upload
