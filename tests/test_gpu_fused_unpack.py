@@ -278,3 +278,40 @@ def test_fused_step_recorded_into_a_graph_and_replayed(orc, mode):
     finally:
         torch.cuda.synchronize()
         psx.psx_ctx_destroy(ctx)
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_lists_alignments_and_modes(orc, seed):
+    """Seeded random tensor lists (empty, single-element and oversized tensors), chunk sizes, tensor alignments,
+    chunk reuse, decay settings and PSX_TUNE_FUSED_UNPACK values: two steps each, compared in full."""
+    rng = np.random.default_rng(seed)
+    C = int(rng.choice([256, 1000, 4104, 8192, 20000]))
+    n = int(rng.integers(1, 12))
+    numel = [int(x) for x in np.maximum(0, np.floor(np.exp(rng.uniform(0, np.log(3 * C), n))).astype(np.int64) - rng.integers(0, 2, n))]
+    if sum(numel) == 0:
+        numel[0] = 5
+    slots, o_slots, used = layout(orc, numel, C)
+    alias = bool(rng.integers(0, 2))
+    cl = ChunkLists(used, C, alias=alias)
+    fill(cl, 100000 + seed, 256.0)
+    gaps = [int(g) for g in rng.integers(0, 5, n)]
+    if rng.random() < 0.3:
+        gaps = [g * 64 for g in gaps]                   # line-aligned tensors now and then
+    tens = Tensors(numel, gaps)
+    ctx = psx.psx_ctx_create(max_chunks=cl.n, max_tensors=len(numel))
+    try:
+        psx.psx_ctx_set_tuning(ctx, psx.PSX_TUNE_FUSED_UNPACK, int(rng.integers(0, 3)))
+        chunks = psx.make_chunks(cl.specs())
+        for step in (1, 2):
+            hp = dict(lr=1e-3, weight_decay=float(rng.choice([0.0, 0.01])), adamw_mode=int(rng.integers(0, 2)), step=step,
+                      loss_scale=256.0)
+            if alias and step == 2:
+                fill(cl, 200000 + seed, 256.0)          # the last step overwrote the gradients with parameters
+            psx.psx_chunk_adam_step_unpack(ctx, chunks, psx.make_hyper(**hp), psx.PSX_STEP_CHECK_FIRST, tens.ptrs, slots, C)
+            torch.cuda.synchronize()
+            assert cl.oracle_step(orc, orc.hyper(**hp)) == 0
+            assert cl.compare(f"step {step}") == 0.0
+            assert np.array_equal(tens.bits(), tens.expect(orc, o_slots, cl.np["p16"], C)), (step, numel, C, gaps)
+    finally:
+        torch.cuda.synchronize()
+        psx.psx_ctx_destroy(ctx)
