@@ -1087,8 +1087,7 @@ int32_t validate_out(psx_ctx *c, const psx_chunk *chunks, size_t n_chunks, const
 // Cuts every tensor into its pieces per chunk, keeps what lies inside the chunk's used prefix (the update
 // produces nothing behind it), orders the pieces by chunk and offset and refuses overlapping ones; then
 // notes for each resident run (c->runs[0 .. n_res), ascending in chunk) where its pieces start.
-int32_t build_out(psx_ctx *c, const psx_chunk *chunks, size_t n_chunks, const OutSpec &o, size_t n_res) {
-    (void)n_chunks;
+int32_t build_out(psx_ctx *c, const psx_chunk *chunks, const OutSpec &o, size_t n_res) {
     c->outs.clear();
     for (size_t i = 0; i < o.n; i++) {
         const uint64_t sz = o.slots[i].numel;
@@ -1212,7 +1211,7 @@ int32_t adam_step_impl(psx_ctx *c, const psx_chunk *chunks, size_t n_chunks, con
     SegView unpack_view{nullptr, nullptr, 0, nullptr, 0};
     uint64_t unpack_tiles = 0;
     if (out != nullptr) {
-        if ((rc = build_out(c, chunks, n_chunks, *out, pl.n_res)) != PSX_OK) return rc;
+        if ((rc = build_out(c, chunks, *out, pl.n_res)) != PSX_OK) return rc;
         uint64_t aligned = 0, covered = 0;
         for (const OutSeg &g : c->outs) {
             covered += g.n;
